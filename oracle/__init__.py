@@ -1,0 +1,165 @@
+"""CPU oracle for the L2-norm KV-cache compression hot path (arXiv 2406.11430).
+
+TEST INFRASTRUCTURE ONLY: tests, the smoke check and the benchmark's
+``cpu_baseline`` leg may import this package; the product never does, and this
+package never imports the product.  It wraps ``l2kv_oracle.c`` (plain C, built
+with gcc) behind NumPy arrays.  bf16 tensors travel as ``uint16`` bit patterns.
+
+Functions, each following the passage named in the C source:
+
+* ``keep_count(T, r)``            -- kept rows k = ceil(r*T) (Sec. 3, |D| = m exact)
+* ``norms(K, dtype)``             -- squared key norms, fp32 fixed order + fp64
+* ``select(n32, k, mode)``        -- lowest-norm positions (Sec. 1 rule), full sort
+* ``compact(X, idx)``             -- gather of kept rows ("and the corresponding values")
+* ``decode_attn(Q, Kc, Vc, ...)`` -- single-query softmax attention (Eq. 2 / Eq. 4)
+* ``compress(K, V, dtype, r)``    -- the three compression steps in sequence
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "l2kv_oracle.c")
+_LIB = os.path.join(_HERE, "libl2kv_oracle.so")
+
+F32, BF16 = 0, 1
+_DT = {"f32": F32, "bf16": BF16, F32: F32, BF16: BF16}
+MODE_LOWEST, MODE_HIGHEST = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (no contraction, no fast-math)."""
+    stale = (not os.path.exists(_LIB)
+             or os.path.getmtime(_LIB) < os.path.getmtime(_SRC))
+    if force or stale:
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.run(
+            ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math",
+             "-Wall", "-Wextra", "-shared", "-fPIC", _SRC, "-o", tmp, "-lm"],
+            check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        c = ctypes
+        lib.l2kv_oracle_keep_count.restype = c.c_int64
+        lib.l2kv_oracle_keep_count.argtypes = [c.c_int64, c.c_double]
+        lib.l2kv_oracle_norms.restype = c.c_int
+        lib.l2kv_oracle_norms.argtypes = [
+            c.c_void_p, c.c_int, c.c_int64, c.c_int64, c.c_int32, c.c_int64,
+            c.c_void_p, c.c_void_p]
+        lib.l2kv_oracle_select.restype = c.c_int
+        lib.l2kv_oracle_select.argtypes = [
+            c.c_void_p, c.c_int64, c.c_int64, c.c_int, c.c_void_p]
+        lib.l2kv_oracle_compact.restype = None
+        lib.l2kv_oracle_compact.argtypes = [
+            c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_void_p]
+        lib.l2kv_oracle_decode_attn.restype = c.c_int
+        lib.l2kv_oracle_decode_attn.argtypes = [
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_int, c.c_int32, c.c_int32,
+            c.c_int32, c.c_int64, c.c_int32, c.c_int64, c.c_double, c.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def _np_dtype(dtype) -> np.dtype:
+    return np.dtype(np.uint16) if _DT[dtype] == BF16 else np.dtype(np.float32)
+
+
+def _check(a: np.ndarray, dtype) -> np.ndarray:
+    want = _np_dtype(dtype)
+    if a.dtype != want:
+        raise TypeError("expected %s array for dtype %r, got %s" % (want, dtype, a.dtype))
+    return np.ascontiguousarray(a)
+
+
+def keep_count(T: int, keep_ratio: float) -> int:
+    return int(_load().l2kv_oracle_keep_count(int(T), float(keep_ratio)))
+
+
+def norms(K: np.ndarray, dtype) -> Tuple[np.ndarray, np.ndarray]:
+    """K ``[..., T, D]`` -> (n32 ``[..., T]`` float32, n64 ``[..., T]`` float64)."""
+    K = _check(K, dtype)
+    *lead, T, D = K.shape
+    n_heads = int(np.prod(lead)) if lead else 1
+    n32 = np.empty((n_heads, T), dtype=np.float32)
+    n64 = np.empty((n_heads, T), dtype=np.float64)
+    rc = _load().l2kv_oracle_norms(K.ctypes.data, _DT[dtype], n_heads, T, D,
+                                   T * D, n32.ctypes.data, n64.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle norms: unsupported shape/dtype (D=%d)" % D)
+    return n32.reshape(*lead, T), n64.reshape(*lead, T)
+
+
+def select(n32: np.ndarray, k: int, mode: int = MODE_LOWEST) -> np.ndarray:
+    """n32 ``[..., T]`` -> kept indices ``[..., k]`` int32, ascending per head."""
+    n32 = np.ascontiguousarray(n32, dtype=np.float32)
+    *lead, T = n32.shape
+    flat = n32.reshape(-1, T)
+    out = np.empty((flat.shape[0], k), dtype=np.int32)
+    lib = _load()
+    for h in range(flat.shape[0]):
+        rc = lib.l2kv_oracle_select(flat[h].ctypes.data, T, k, mode,
+                                    out[h].ctypes.data)
+        if rc != 0:
+            raise ValueError("oracle select failed (rc=%d, T=%d, k=%d)" % (rc, T, k))
+    return out.reshape(*lead, k)
+
+
+def compact(X: np.ndarray, kept_idx: np.ndarray) -> np.ndarray:
+    """X ``[..., T, D]``, kept_idx ``[..., k]`` -> ``[..., k, D]`` (byte copy)."""
+    X = np.ascontiguousarray(X)
+    kept_idx = np.ascontiguousarray(kept_idx, dtype=np.int32)
+    *lead, T, D = X.shape
+    k = kept_idx.shape[-1]
+    Xf = X.reshape(-1, T, D)
+    If = kept_idx.reshape(-1, k)
+    assert Xf.shape[0] == If.shape[0]
+    if k and (If.min() < 0 or If.max() >= T):
+        raise IndexError("kept index out of range")
+    out = np.empty((Xf.shape[0], k, D), dtype=X.dtype)
+    lib = _load()
+    for h in range(Xf.shape[0]):
+        lib.l2kv_oracle_compact(Xf[h].ctypes.data, If[h].ctypes.data, k,
+                                D * X.dtype.itemsize, out[h].ctypes.data)
+    return out.reshape(*lead, k, D)
+
+
+def decode_attn(Q: np.ndarray, Kc: np.ndarray, Vc: np.ndarray, dtype,
+                scale: float = 0.0) -> np.ndarray:
+    """Q ``[B, Hq, D]``, Kc/Vc ``[B, Hkv, n, D]`` -> O ``[B, Hq, D]`` float32."""
+    Q = _check(Q, dtype)
+    Kc = _check(Kc, dtype)
+    Vc = _check(Vc, dtype)
+    B, Hq, D = Q.shape
+    Bk, Hkv, n, Dk = Kc.shape
+    assert (Bk, Dk) == (B, D) and Vc.shape == Kc.shape
+    O = np.empty((B, Hq, D), dtype=np.float32)
+    rc = _load().l2kv_oracle_decode_attn(
+        Q.ctypes.data, Kc.ctypes.data, Vc.ctypes.data, _DT[dtype], B, Hq, Hkv,
+        n, D, n * D, float(scale), O.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle decode_attn: bad arguments (rc=%d)" % rc)
+    return O
+
+
+def compress(K: np.ndarray, V: np.ndarray, dtype, keep_ratio: float,
+             mode: int = MODE_LOWEST, k: Optional[int] = None):
+    """norms -> select -> compact.  Returns (n32, n64, kept_idx, Kc, Vc)."""
+    n32, n64 = norms(K, dtype)
+    if k is None:
+        k = keep_count(K.shape[-2], keep_ratio)
+    idx = select(n32, k, mode)
+    return n32, n64, idx, compact(K, idx), compact(V, idx)

@@ -1,0 +1,419 @@
+"""Pins for the CPU oracle: everything here checks ``oracle/`` against something
+other than itself -- hand-derived fixtures, closed forms, brute force on tiny
+inputs, invariants of the method, and library routines on special cases.
+No GPU needed."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+
+# ----------------------------------------------------------------- helpers
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 -> bf16 bit patterns with torch (library conversion)."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16)
+    return t.view(torch.int16).numpy().view(np.uint16)
+
+
+def bf16_to_f64(b: np.ndarray) -> np.ndarray:
+    return (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def parse_golden(path):
+    out = {}
+    with open(path) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, val = line.split("=", 1)
+            out[key.strip()] = [float(v) for v in val.split()]
+    return out
+
+
+def brute_force_kept(n32_row: np.ndarray, k: int) -> np.ndarray:
+    """Rank counting, no sort: position i is kept iff fewer than k positions
+    precede it in (bits, index) order."""
+    bits = n32_row.view(np.uint32)
+    T = len(bits)
+    kept = []
+    for i in range(T):
+        rank = 0
+        for j in range(T):
+            if bits[j] < bits[i] or (bits[j] == bits[i] and j < i):
+                rank += 1
+        if rank < k:
+            kept.append(i)
+    return np.array(kept, dtype=np.int32)
+
+
+# -------------------------------------------------------------- keep_count
+@pytest.mark.parametrize("T,r,k", [
+    (512, 0.5, 256), (4096, 0.5, 2048), (32768, 0.5, 16384),
+    (131072, 0.1, 13108),        # 13107.2 -> ceil
+    (100, 0.55, 55),             # 55.000000000000007 is 55, not 56
+    (100, 0.07, 7),              # 7.000000000000001
+    (10, 0.3, 3),                # 3 (binary 0.3*10 = 3.0000000000000004)
+    (7, 0.5, 4),                 # 3.5 -> 4
+    (8, 0.3, 3),                 # 2.4 -> 3
+    (8, 1.0, 8), (1, 0.01, 1), (1000, 1e-9, 1),
+    (3, 0.999, 3), (0, 0.5, 0),
+])
+def test_keep_count_values(T, r, k):
+    assert oracle.keep_count(T, r) == k
+
+
+def test_keep_count_monotone_and_bounded():
+    for T in (1, 2, 5, 64, 1000):
+        prev = 0
+        for r in np.linspace(0.001, 1.0, 400):
+            k = oracle.keep_count(T, float(r))
+            assert 1 <= k <= T and k >= prev
+            assert k >= r * T - 1e-6 and k < r * T + 1 + 1e-6
+            prev = k
+
+
+# -------------------------------------------------------------------- norms
+def test_norm_fixed_order_golden(golden_dir):
+    n_cases = 0
+    with open(os.path.join(golden_dir, "norm_order_cases.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            name, dt, D, sparse, want = [s.strip() for s in line.split("|")]
+            D = int(D)
+            row = np.zeros((1, D), dtype=np.float32)
+            for item in sparse.split():
+                i, v = item.split(":")
+                row[0, int(i)] = float(v)
+            K = bf16_bits(row) if dt == "bf16" else row
+            n32, n64 = oracle.norms(K, dt)
+            assert n32.dtype == np.float32
+            assert float(n32[0]) == float(want), name
+            assert n64[0] == float((row.astype(np.float64) ** 2).sum()), name
+            # the case really discriminates: a left-to-right fp32 sum differs
+            naive = np.float32(0)
+            for v in row[0]:
+                naive = np.float32(naive + np.float32(v * v))
+            assert float(naive) != float(want), name
+            n_cases += 1
+    assert n_cases >= 5
+
+
+@pytest.mark.parametrize("dt,D", [("f32", 64), ("f32", 128), ("bf16", 64), ("bf16", 128)])
+def test_norm_small_integers_exact(dt, D):
+    # integer keys in [-8, 8]: every partial sum is an exact small integer in
+    # fp32 whatever the order, so the result must equal the integer sum.
+    rng = np.random.default_rng(5)
+    Ki = rng.integers(-8, 9, size=(3, 37, D))
+    K = Ki.astype(np.float32)
+    Kin = bf16_bits(K) if dt == "bf16" else K
+    n32, n64 = oracle.norms(Kin, dt)
+    want = (Ki.astype(np.int64) ** 2).sum(-1)
+    assert np.array_equal(n32.astype(np.int64), want)
+    assert np.array_equal(n64, want.astype(np.float64))
+
+
+@pytest.mark.parametrize("dt,D", [("f32", 64), ("bf16", 128)])
+def test_norm_close_to_fp64_and_numpy(dt, D):
+    rng = np.random.default_rng(11)
+    K = (rng.standard_normal((2, 2, 100, D)) *
+         np.exp(0.5 * rng.standard_normal((2, 2, 100, 1)))).astype(np.float32)
+    if dt == "bf16":
+        Kin = bf16_bits(K)
+        Kd = bf16_to_f64(Kin)
+    else:
+        Kin, Kd = K, K.astype(np.float64)
+    n32, n64 = oracle.norms(Kin, dt)
+    truth = (Kd ** 2).sum(-1)
+    assert n32.shape == truth.shape
+    np.testing.assert_allclose(n64, truth, rtol=1e-14)
+    # fp32 tree sum: error bounded by (depth+1) half-ulps of the result
+    np.testing.assert_allclose(n32, truth, rtol=(D // 16 + 5) * 2.0 ** -24)
+
+
+def test_norm_single_coordinate_closed_form():
+    # K_t = c_t e_{t mod D}: squared norm is c_t^2 (one rounding for fp32).
+    D, T = 64, 130
+    c = np.linspace(0.1, 9.0, T).astype(np.float32)
+    K = np.zeros((1, T, D), dtype=np.float32)
+    K[0, np.arange(T), np.arange(T) % D] = c
+    n32, _ = oracle.norms(K, "f32")
+    assert np.array_equal(n32[0], (c * c).astype(np.float32))
+
+
+def test_norm_power_of_two_scaling_is_exact():
+    rng = np.random.default_rng(3)
+    K = rng.standard_normal((1, 50, 128)).astype(np.float32)
+    a, _ = oracle.norms(K, "f32")
+    b, _ = oracle.norms(K * np.float32(4.0), "f32")
+    assert np.array_equal(b, a * np.float32(16.0))
+
+
+# ---------------------------------------------------------------- selection
+@pytest.mark.parametrize("seed", range(6))
+def test_select_matches_brute_force_rank_counting(seed):
+    rng = np.random.default_rng(seed)
+    T = int(rng.integers(1, 65))
+    # few distinct values -> many ties
+    vals = rng.choice(np.array([0.0, 0.25, 1.0, 1.5, 7.0, np.inf], dtype=np.float32), size=T)
+    if seed % 2:
+        vals = rng.random(T).astype(np.float32)
+    for k in sorted({1, T, max(1, T // 2), max(1, T // 3)}):
+        got = oracle.select(vals[None, :], k)[0]
+        assert np.array_equal(got, brute_force_kept(vals, k))
+
+
+def test_select_all_equal_norms_is_pure_tiebreak():
+    n = np.full((2, 33), 3.5, dtype=np.float32)
+    assert np.array_equal(oracle.select(n, 10), np.tile(np.arange(10, dtype=np.int32), (2, 1)))
+    # highest-norm mode breaks ties the same way
+    assert np.array_equal(oracle.select(n, 10, oracle.MODE_HIGHEST),
+                          np.tile(np.arange(10, dtype=np.int32), (2, 1)))
+
+
+def test_select_matches_stable_argsort_and_topk():
+    rng = np.random.default_rng(42)
+    n = rng.random((5, 777)).astype(np.float32)
+    n[:, ::7] = n[:, 3:4]                       # inject ties
+    k = 300
+    got = oracle.select(n, k)
+    for h in range(n.shape[0]):
+        want = np.sort(np.argsort(n[h], kind="stable")[:k]).astype(np.int32)
+        assert np.array_equal(got[h], want)
+    # torch.topk agrees on the VALUES kept (tie order is its own business)
+    tv = torch.topk(torch.from_numpy(n), k, dim=1, largest=False).values.sort(dim=1).values.numpy()
+    gv = np.sort(np.take_along_axis(n, got, axis=1), axis=1)
+    assert np.array_equal(tv, gv)
+
+
+def test_select_invariants():
+    rng = np.random.default_rng(8)
+    T = 500
+    n = np.exp(rng.standard_normal((4, T))).astype(np.float32)
+    bits = n.view(np.uint32).astype(np.int64)
+    prev = None
+    for r in (0.1, 0.37, 0.5, 0.9, 1.0):
+        k = oracle.keep_count(T, r)
+        idx = oracle.select(n, k)
+        assert idx.shape == (4, k)
+        for h in range(4):
+            kept = idx[h]
+            assert np.all(np.diff(kept) > 0)               # strictly ascending
+            mask = np.zeros(T, bool)
+            mask[kept] = True
+            if k < T:                                      # threshold property
+                key = bits[h] * T + np.arange(T)
+                assert key[mask].max() < key[~mask].min()
+        if prev is not None:                               # nesting
+            for h in range(4):
+                assert set(prev[h]).issubset(set(idx[h]))
+        prev = idx
+    assert np.array_equal(oracle.select(n, T), np.tile(np.arange(T, dtype=np.int32), (4, 1)))
+
+
+def test_select_token_permutation_equivariance_and_pow2_scale():
+    rng = np.random.default_rng(9)
+    T, k = 301, 77
+    n = rng.random((1, T)).astype(np.float32)          # distinct with prob. 1
+    assert len(np.unique(n)) == T
+    base = set(oracle.select(n, k)[0])
+    perm = rng.permutation(T)
+    n_perm = n[:, perm]                                # new position j holds old perm[j]
+    got = oracle.select(n_perm, k)[0]
+    assert {int(perm[j]) for j in got} == base
+    assert set(oracle.select(n * np.float32(0.25), k)[0]) == base
+
+
+def test_select_highest_is_complement_of_lowest_when_distinct():
+    rng = np.random.default_rng(10)
+    T, k = 200, 60
+    n = rng.random((3, T)).astype(np.float32)
+    hi = oracle.select(n, k, oracle.MODE_HIGHEST)
+    lo = oracle.select(n, T - k, oracle.MODE_LOWEST)
+    for h in range(3):
+        assert set(hi[h]) | set(lo[h]) == set(range(T))
+        assert not (set(hi[h]) & set(lo[h]))
+
+
+def test_select_inf_and_nan_patterns_evicted_first():
+    n = np.array([[1.0, np.inf, 0.5, np.nan, 2.0, 0.0]], dtype=np.float32)
+    assert list(oracle.select(n, 4)[0]) == [0, 2, 4, 5]
+    assert list(oracle.select(n, 5)[0]) == [0, 1, 2, 4, 5]   # inf before nan
+
+
+# --------------------------------------------------------------- compaction
+def test_compact_is_a_row_gather():
+    rng = np.random.default_rng(1)
+    X = rng.integers(0, 65536, size=(2, 3, 50, 128)).astype(np.uint16)
+    idx = np.sort(rng.permuted(np.tile(np.arange(50), (2, 3, 1)), axis=-1)[..., :20], axis=-1).astype(np.int32)
+    got = oracle.compact(X, idx)
+    want = np.take_along_axis(X, idx[..., None].astype(np.int64), axis=2)
+    assert got.dtype == X.dtype and np.array_equal(got, want)
+    with pytest.raises(IndexError):
+        oracle.compact(X, np.full((2, 3, 1), 50, dtype=np.int32))
+
+
+# ---------------------------------------------------------------- attention
+def _rand_case(rng, B, Hq, Hkv, n, D, dt):
+    Q = rng.standard_normal((B, Hq, D)).astype(np.float32)
+    K = rng.standard_normal((B, Hkv, n, D)).astype(np.float32)
+    V = rng.standard_normal((B, Hkv, n, D)).astype(np.float32)
+    if dt == "bf16":
+        return bf16_bits(Q), bf16_bits(K), bf16_bits(V)
+    return Q, K, V
+
+
+def _as_f64(x, dt):
+    return bf16_to_f64(x) if dt == "bf16" else x.astype(np.float64)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Hq,Hkv,n,D", [(2, 8, 2, 37, 64), (1, 4, 4, 5, 128), (3, 6, 3, 64, 16)])
+def test_attention_matches_numpy_and_torch_fp64(dt, B, Hq, Hkv, n, D):
+    rng = np.random.default_rng(B * 100 + n)
+    Q, K, V = _rand_case(rng, B, Hq, Hkv, n, D, dt)
+    got = oracle.decode_attn(Q, K, V, dt)
+    q, k, v = _as_f64(Q, dt), _as_f64(K, dt), _as_f64(V, dt)
+    G = Hq // Hkv
+    # explicit repeat: query head hq uses KV head hq // G
+    kk = np.repeat(k, G, axis=1)
+    vv = np.repeat(v, G, axis=1)
+    s = np.einsum("bhd,bhnd->bhn", q, kk) / np.sqrt(D)
+    p = np.exp(s - s.max(-1, keepdims=True))
+    p /= p.sum(-1, keepdims=True)
+    want = np.einsum("bhn,bhnd->bhd", p, vv)
+    np.testing.assert_allclose(got, want, rtol=0, atol=2e-7 * max(1.0, np.abs(want).max()))
+    # library routine: torch scaled_dot_product_attention in fp64 on the CPU
+    t = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q)[:, :, None, :], torch.from_numpy(kk), torch.from_numpy(vv))
+    np.testing.assert_allclose(got, t[:, :, 0, :].numpy(), rtol=0,
+                               atol=2e-7 * max(1.0, np.abs(want).max()))
+
+
+def test_attention_gqa_mapping_is_consecutive_groups():
+    # KV head j holds V rows all equal to j: output of query head hq must be hq // G.
+    B, Hq, Hkv, n, D = 1, 8, 2, 9, 64
+    rng = np.random.default_rng(2)
+    Q = rng.standard_normal((B, Hq, D)).astype(np.float32)
+    K = rng.standard_normal((B, Hkv, n, D)).astype(np.float32)
+    V = np.zeros((B, Hkv, n, D), dtype=np.float32)
+    V[0, 1] = 1.0
+    got = oracle.decode_attn(Q, K, V, "f32")
+    want = (np.arange(Hq) // (Hq // Hkv)).astype(np.float32)
+    np.testing.assert_allclose(got[0, :, 0], want, atol=1e-7)
+    np.testing.assert_allclose(got[0], np.repeat(want[:, None], D, 1), atol=1e-7)
+
+
+def test_attention_closed_forms():
+    rng = np.random.default_rng(4)
+    B, Hq, Hkv, n, D = 2, 4, 2, 23, 64
+    Q, K, V = _rand_case(rng, B, Hq, Hkv, n, D, "f32")
+    # (1) zero keys or zero query -> plain mean of the value rows
+    mean_v = np.repeat(V.astype(np.float64).mean(2), Hq // Hkv, axis=1)
+    np.testing.assert_allclose(oracle.decode_attn(Q, np.zeros_like(K), V, "f32"), mean_v, atol=1e-6)
+    np.testing.assert_allclose(oracle.decode_attn(np.zeros_like(Q), K, V, "f32"), mean_v, atol=1e-6)
+    # (2) all value rows equal -> that row
+    v0 = rng.standard_normal(D).astype(np.float32)
+    Vc = np.broadcast_to(v0, V.shape).copy()
+    np.testing.assert_allclose(oracle.decode_attn(Q, K, Vc, "f32"),
+                               np.broadcast_to(v0, (B, Hq, D)), atol=1e-6)
+    # (3) one key aligned with q at a large scale -> its value row
+    K3 = K.copy()
+    for b in range(B):
+        for hkv in range(Hkv):
+            K3[b, hkv, 7] = 50.0 * Q[b, hkv * (Hq // Hkv)]
+    got = oracle.decode_attn(Q, K3, V, "f32")
+    for b in range(B):
+        for hkv in range(Hkv):
+            np.testing.assert_allclose(got[b, hkv * (Hq // Hkv)], V[b, hkv, 7], atol=1e-5)
+    # (4) explicit scale: scale=1/sqrt(D) equals the default; doubling it differs
+    d0 = oracle.decode_attn(Q, K, V, "f32")
+    d1 = oracle.decode_attn(Q, K, V, "f32", scale=1.0 / np.sqrt(D))
+    np.testing.assert_allclose(d0, d1, atol=1e-7)
+    assert np.abs(oracle.decode_attn(Q, K, V, "f32", scale=2.0 / np.sqrt(D)) - d0).max() > 1e-3
+    # (5) a constant added to every logit changes nothing: append a coordinate
+    #     block (constant in K, 1 in q); D grows from 64 to 128, scale held fixed.
+    Kx = np.concatenate([K, np.zeros_like(K)], axis=-1)
+    Kx[..., D] = 3.0
+    Qx = np.concatenate([Q, np.zeros_like(Q)], axis=-1)
+    Qx[..., D] = 1.0
+    Vx = np.concatenate([V, V], axis=-1)
+    dx = oracle.decode_attn(Qx, Kx, Vx, "f32", scale=1.0 / np.sqrt(D))
+    np.testing.assert_allclose(dx[..., :D], d0, atol=1e-6)
+    # (6) permuting the cached rows (K and V together) changes nothing
+    perm = rng.permutation(n)
+    np.testing.assert_allclose(oracle.decode_attn(Q, K[:, :, perm], V[:, :, perm], "f32"), d0, atol=1e-6)
+
+
+def test_attention_two_rows_is_a_sigmoid():
+    # n = 2: weights are sigmoid(+-(s0-s1)); check against math.exp directly.
+    D = 16
+    q = np.zeros((1, 1, D), np.float32)
+    q[0, 0, 0] = 4.0                        # / sqrt(16) -> logit = K[.,0]
+    K = np.zeros((1, 1, 2, D), np.float32)
+    K[0, 0, 0, 0], K[0, 0, 1, 0] = 1.0, -0.5
+    V = np.zeros((1, 1, 2, D), np.float32)
+    V[0, 0, 0, :], V[0, 0, 1, :] = 2.0, -1.0
+    w0 = 1.0 / (1.0 + np.exp(-1.5))
+    got = oracle.decode_attn(q, K, V, "f32")
+    np.testing.assert_allclose(got[0, 0], np.full(D, 2.0 * w0 - 1.0 * (1 - w0)), atol=1e-7)
+
+
+# ------------------------------------------------------------ whole pipeline
+def test_worked_example(golden_dir):
+    g = parse_golden(os.path.join(golden_dir, "worked_example.txt"))
+    T, D = 8, 16
+    c = np.array(g["c"], dtype=np.float32)
+    w = np.array(g["w"], dtype=np.float64)
+    K = np.zeros((1, 1, T, D), np.float32)
+    K[0, 0, np.arange(T), np.arange(T)] = c
+    V = np.zeros((1, 1, T, D), np.float32)
+    for t in range(T):
+        V[0, 0, t, :] = t + 1
+        V[0, 0, t, t] += 10
+    Q = np.zeros((1, 1, D), np.float32)
+    Q[0, 0, :T] = (4.0 * np.log(w) / c.astype(np.float64)).astype(np.float32)
+
+    n32, n64 = oracle.norms(K, "f32")
+    assert np.array_equal(n32[0, 0], np.array(g["norm2"], np.float32))
+    for r, key in ((0.5, "kept_r0.5"), (0.25, "kept_r0.25"), (0.3, "kept_r0.3")):
+        k = oracle.keep_count(T, r)
+        assert k == len(g[key])
+        assert list(oracle.select(n32, k)[0, 0]) == [int(v) for v in g[key]]
+    assert list(oracle.select(n32, 3, oracle.MODE_HIGHEST)[0, 0]) == [int(v) for v in g["kept_high_3"]]
+
+    _, _, idx, Kc, Vc = oracle.compress(K, V, "f32", 0.5)
+    assert np.array_equal(Kc[0, 0], K[0, 0, idx[0, 0]])
+    assert np.array_equal(Vc[0, 0], V[0, 0, idx[0, 0]])
+    out = oracle.decode_attn(Q, Kc, Vc, "f32")
+    np.testing.assert_allclose(out[0, 0], np.array(g["out_r0.5"]), atol=2e-6)
+    _, _, idx1, Kc1, Vc1 = oracle.compress(K, V, "f32", 1.0)
+    assert np.array_equal(idx1[0, 0], np.arange(T))
+    assert np.array_equal(Kc1, K) and np.array_equal(Vc1, V)
+    out1 = oracle.decode_attn(Q, Kc1, Vc1, "f32")
+    np.testing.assert_allclose(out1[0, 0], np.array(g["out_r1.0"]), atol=2e-6)
+
+
+def test_kept_set_ignores_values_and_queries_and_keep1_is_full_attention():
+    from paper_2406_11430_amd import synth
+    cfg = synth.CONFIGS["C1"].scaled(T=96)
+    K, V = synth.make_layer(cfg, 0)
+    Kn, Vn = synth.as_numpy_bits(K), synth.as_numpy_bits(V)
+    _, _, idx, Kc, Vc = oracle.compress(Kn, Vn, "f32", 0.5)
+    assert idx.shape[-1] == 48
+    rng = np.random.default_rng(0)
+    V2 = rng.permuted(Vn, axis=2)
+    _, _, idx2, _, _ = oracle.compress(Kn, V2, "f32", 0.5)
+    assert np.array_equal(idx, idx2)
+    # sinks (first four tokens, keys scaled by 0.1) survive in every head
+    assert np.all(idx[..., :4] == np.arange(4))
+    Q = synth.as_numpy_bits(synth.make_query(cfg, 0, 0))
+    _, _, _, K1, V1 = oracle.compress(Kn, Vn, "f32", 1.0)
+    np.testing.assert_array_equal(oracle.decode_attn(Q, K1, V1, "f32"),
+                                  oracle.decode_attn(Q, Kn, Vn, "f32"))

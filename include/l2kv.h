@@ -1,0 +1,176 @@
+/*
+ * l2kv -- L2-norm KV-cache compression and decode attention for AMD MI355X
+ * (CDNA4, gfx950).  C ABI of libl2kv.so.
+ *
+ * Method: arXiv 2406.11430, "A Simple and Effective L2 Norm-Based Strategy for
+ * KV Cache Compression".  Its rule (Sec. 1, Sec. 3): per layer and head, keep
+ * the cached keys with the lowest L2 norm together with their values and drop
+ * the rest; decoding then runs ordinary scaled dot-product attention (Eq. 2,
+ * in the decode form of Eq. 4) over the smaller cache.
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ *  - All tensor pointers are DEVICE pointers unless a parameter name starts
+ *    with h_.  The caller owns every buffer; the library never allocates,
+ *    frees, synchronises or copies to the host.
+ *  - Every call only enqueues work on `stream` (a hipStream_t passed as
+ *    void*; NULL = the default stream) and returns.
+ *  - Arguments are validated on the host BEFORE anything is enqueued; a
+ *    negative status means nothing was launched and no device memory was
+ *    touched.  L2KV_ERR_LAUNCH wraps a failed kernel launch.
+ *  - "Head" means one (layer, sequence, KV head) triple.  The rule is
+ *    independent per layer and head (Eq. 5: the dropped set D_{l,h}), so any
+ *    number of layers / sequences can be flattened into n_heads.
+ *  - A K or V row is D contiguous elements; head i starts `head_stride`
+ *    ELEMENTS after head i-1 (head_stride >= T*D).  Supported:
+ *    D in {64, 128}, dtype in {fp32, bf16}.  Base pointers of K, V, Kc, Vc, Q
+ *    must be 16-byte aligned and head_stride*sizeof(elem) a multiple of 16;
+ *    norms / index / O / workspace pointers 4-byte aligned (workspace 16).
+ *  - Outputs must not alias inputs.
+ *  - No global mutable state besides a per-device cache of the compute-unit
+ *    count; calls are thread-safe.
+ */
+#ifndef L2KV_H
+#define L2KV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { L2KV_F32 = 0, L2KV_BF16 = 1 } l2kv_dtype;
+
+typedef enum {
+    L2KV_OK = 0,
+    L2KV_ERR_NULL = -1,      /* a required pointer is NULL                     */
+    L2KV_ERR_SHAPE = -2,     /* a size is <= 0, too large, or D unsupported    */
+    L2KV_ERR_DTYPE = -3,     /* dtype is not L2KV_F32 / L2KV_BF16              */
+    L2KV_ERR_RATIO = -4,     /* keep_ratio outside (0, 1] or not finite        */
+    L2KV_ERR_WORKSPACE = -5, /* workspace NULL or smaller than *_workspace_bytes */
+    L2KV_ERR_ALIGN = -6,     /* pointer or stride alignment violated           */
+    L2KV_ERR_LAUNCH = -7     /* the HIP runtime refused a launch               */
+} l2kv_status;
+
+/* Eviction strategy.  LOWEST is the paper's method; HIGHEST is the control of
+ * Sec. 4 ("keeping tokens with highest L2 norm"). */
+typedef enum { L2KV_KEEP_LOWEST = 0, L2KV_KEEP_HIGHEST = 1 } l2kv_mode;
+
+/*
+ * Number of rows kept out of T at keep_ratio r: k = ceil(r*T), clamped to
+ * [1, T]; a product r*T within 1e-9 relative of an integer counts as that
+ * integer (so 0.55*100 -> 55).  The paper fixes only that the count is exact
+ * (|D_{l,h}| = m, Eq. 5) and quotes "compression ratios" X (Sec. 4), which
+ * are r = 1 - X.  Host function; returns 0 for T <= 0 or r outside (0,1].
+ */
+int64_t l2kv_keep_count(int64_t T, double keep_ratio);
+
+/*
+ * Squared L2 norm of every cached key (the quantity the rule of Sec. 1 /
+ * Sec. 3 ranks by; the square keeps the order and needs no sqrt):
+ *     norms[i][t] = sum_d K[i][t][d]^2          fp32
+ * summed in a fixed order so the result is reproducible bit for bit: the row
+ * is cut into 16 chunks of D/16 consecutive elements, each chunk is summed
+ * left to right, and the 16 partial sums are added as a balanced binary tree
+ * over neighbours; every product and sum is rounded to fp32 separately.
+ *   K      in : n_heads slabs of T rows (layout above), read once
+ *   norms  out: [n_heads][T] fp32, dense
+ * Errors: NULL, SHAPE (n_heads, T <= 0; T > 2^31-1; D; head_stride < T*D),
+ * DTYPE, ALIGN, LAUNCH.
+ */
+l2kv_status l2kv_norms(const void* K, l2kv_dtype dt, int64_t n_heads, int64_t T,
+                       int32_t D, int64_t head_stride, float* norms, void* stream);
+
+/*
+ * Selection (Sec. 1: "keeping in memory only the keys with lowest L2 norm";
+ * Eq. 5: exactly m pairs dropped per layer and head).  For every head, the
+ * k = l2kv_keep_count(T, keep_ratio) positions that come first in the total
+ * order (uint32 bit pattern of the fp32 squared norm, token index) -- ties go
+ * to the lower token index -- written in ascending token order.
+ *   norms      in : [n_heads][T] fp32 (>= +0; +Inf / NaN patterns sort last)
+ *   kept_idx   out: [n_heads][k] int32, strictly ascending per head
+ *   kept_count out: [n_heads] int32, every entry = k; may be NULL
+ *   workspace     : l2kv_select_workspace_bytes(n_heads, T) bytes, 16-aligned;
+ *                   contents need not be initialised and are undefined after
+ * Errors: NULL, SHAPE, RATIO, WORKSPACE, ALIGN, LAUNCH.
+ */
+l2kv_status l2kv_select(const float* norms, int64_t n_heads, int64_t T,
+                        double keep_ratio, int32_t* kept_idx, int32_t* kept_count,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same with an explicit kept count k (1 <= k <= T) and strategy.  HIGHEST
+ * orders by descending norm, ties again to the lower token index. */
+l2kv_status l2kv_select_k(const float* norms, int64_t n_heads, int64_t T,
+                          int64_t k, l2kv_mode mode, int32_t* kept_idx,
+                          int32_t* kept_count, void* workspace,
+                          size_t workspace_bytes, void* stream);
+
+size_t l2kv_select_workspace_bytes(int64_t n_heads, int64_t T);
+
+/*
+ * Compaction ("...and the corresponding values", Sec. 1): the kept rows of K
+ * and of V copied, byte for byte and in the order of kept_idx, into dense
+ * caches:
+ *     Kc[i][j][:] = K[i][kept_idx[i][j]][:],   Vc likewise.
+ *   K, V     in : n_heads slabs of T rows (layout above); dropped rows are
+ *                 never read.  V may be NULL together with Vc (K only).
+ *   kept_idx in : [n_heads][k] int32, every entry in [0, T) (not checked on
+ *                 the device: indices outside that range read out of bounds)
+ *   Kc, Vc   out: [n_heads][k][D], dense
+ * Errors: NULL, SHAPE (k <= 0, k > T, ...), DTYPE, ALIGN, LAUNCH.
+ */
+l2kv_status l2kv_compact(const void* K, const void* V, l2kv_dtype dt,
+                         const int32_t* kept_idx, int64_t n_heads, int64_t T,
+                         int64_t k, int32_t D, int64_t head_stride,
+                         void* Kc, void* Vc, void* stream);
+
+/*
+ * Decode attention (Eq. 2 for a single query row; Eq. 4: the query attends to
+ * every row of the cache it is handed, the current token's row included by
+ * the caller).  For each sequence b and query head hq, with KV head
+ * hkv = hq / (Hq/Hkv) (consecutive query heads share a KV head):
+ *     O[b][hq][:] = softmax_j( scale * Q[b][hq] . Kc[b][hkv][j] ) . Vc[b][hkv]
+ * over j in [0, kv_len).  No mask.  Scores are never written to memory: the
+ * cache is streamed once per KV head for all Hq/Hkv query heads, split over
+ * row ranges with an online softmax, and the partial results are merged.
+ *   Q   in : [B][Hq][D], dtype dt
+ *   Kc,Vc in: (b,hkv) slab starts (b*Hkv+hkv)*kv_head_stride elements in;
+ *             kv_len rows of D
+ *   scale  : softmax scale; <= 0 selects 1/sqrt(D) (Eq. 2)
+ *   O   out: [B][Hq][D] fp32
+ *   workspace: l2kv_decode_workspace_bytes(B, Hq, kv_len, D) bytes,
+ *              16-aligned, uninitialised; holds the split partials
+ * Arithmetic: products and sums in fp32 (bf16 inputs widened exactly).
+ * Errors: NULL, SHAPE (Hq % Hkv != 0, Hq/Hkv > 8, kv_len <= 0, ...), DTYPE,
+ * WORKSPACE, ALIGN, LAUNCH.
+ */
+l2kv_status l2kv_decode_attn(const void* Q, const void* Kc, const void* Vc,
+                             l2kv_dtype dt, int32_t B, int32_t Hq, int32_t Hkv,
+                             int64_t kv_len, int32_t D, int64_t kv_head_stride,
+                             float scale, float* O, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+/* Same with the number of row ranges per KV head chosen by the caller
+ * (1 <= n_splits <= l2kv_decode_max_splits(kv_len); 0 = library default).
+ * The result does not depend on n_splits beyond fp32 rounding. */
+l2kv_status l2kv_decode_attn_splits(const void* Q, const void* Kc, const void* Vc,
+                                    l2kv_dtype dt, int32_t B, int32_t Hq, int32_t Hkv,
+                                    int64_t kv_len, int32_t D, int64_t kv_head_stride,
+                                    float scale, int32_t n_splits, float* O,
+                                    void* workspace, size_t workspace_bytes,
+                                    void* stream);
+
+int32_t l2kv_decode_max_splits(int64_t kv_len);
+size_t  l2kv_decode_workspace_bytes(int32_t B, int32_t Hq, int64_t kv_len, int32_t D);
+
+/* Static, NUL-terminated description of a status code. */
+const char* l2kv_status_string(l2kv_status s);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t l2kv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* L2KV_H */

@@ -1,0 +1,12 @@
+"""L2-norm KV-cache compression and decode attention for AMD MI355X (gfx950).
+
+Python face of libl2kv.so (see include/l2kv.h): the functions below have the
+names of the C entry points and only marshal arguments.  ``synth`` holds the
+seeded input generators and none of the method's arithmetic.
+"""
+from .binding import (  # noqa: F401
+    L2KV_BF16, L2KV_F32, L2KV_KEEP_HIGHEST, L2KV_KEEP_LOWEST, L2KVError, LIB_PATH, lib,
+    l2kv_compact, l2kv_decode_attn, l2kv_decode_attn_splits, l2kv_decode_max_splits,
+    l2kv_decode_workspace_bytes, l2kv_keep_count, l2kv_norms, l2kv_select, l2kv_select_k,
+    l2kv_select_workspace_bytes, l2kv_version,
+)

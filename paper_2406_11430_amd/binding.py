@@ -1,0 +1,209 @@
+"""ctypes binding of libl2kv.so: one Python function per C entry point, same
+names, argument marshalling only.  Tensors are torch CUDA(HIP) tensors used as
+device memory; every step of the path runs inside the library's kernels.
+
+The library must already be built (``python -m paper_2406_11430_amd.build``);
+nothing here falls back to another implementation.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libl2kv.so")
+
+L2KV_F32, L2KV_BF16 = 0, 1
+L2KV_KEEP_LOWEST, L2KV_KEEP_HIGHEST = 0, 1
+L2KV_OK = 0
+
+# name -> (restype, argtypes); mirrors include/l2kv.h declaration by declaration
+SIGNATURES = {
+    "l2kv_keep_count": (C.c_int64, [C.c_int64, C.c_double]),
+    "l2kv_norms": (C.c_int, [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int32, C.c_int64,
+                             C.c_void_p, C.c_void_p]),
+    "l2kv_select": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_double, C.c_void_p, C.c_void_p,
+                              C.c_void_p, C.c_size_t, C.c_void_p]),
+    "l2kv_select_k": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_void_p,
+                                C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "l2kv_select_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64]),
+    "l2kv_compact": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int64, C.c_int64,
+                               C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "l2kv_decode_attn": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32,
+                                   C.c_int32, C.c_int64, C.c_int32, C.c_int64, C.c_float, C.c_void_p,
+                                   C.c_void_p, C.c_size_t, C.c_void_p]),
+    "l2kv_decode_attn_splits": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int32,
+                                          C.c_int32, C.c_int32, C.c_int64, C.c_int32, C.c_int64,
+                                          C.c_float, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
+                                          C.c_void_p]),
+    "l2kv_decode_max_splits": (C.c_int32, [C.c_int64]),
+    "l2kv_decode_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int64, C.c_int32]),
+    "l2kv_status_string": (C.c_char_p, [C.c_int]),
+    "l2kv_version": (C.c_int32, []),
+}
+
+
+class L2KVError(RuntimeError):
+    def __init__(self, fn: str, status: int, text: str):
+        super().__init__("%s failed: status %d (%s)" % (fn, status, text))
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded libl2kv.so; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libl2kv.so is missing at %s: build it with "
+                "`python -m paper_2406_11430_amd.build` (there is no fallback path)" % LIB_PATH)
+        handle = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def _check(fn: str, status: int) -> None:
+    if status != L2KV_OK:
+        raise L2KVError(fn, status, lib().l2kv_status_string(status).decode())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return L2KV_F32
+    if t.dtype == torch.bfloat16:
+        return L2KV_BF16
+    raise TypeError("l2kv supports float32 and bfloat16 caches, got %s" % t.dtype)
+
+
+def _dev(*tensors: Optional[torch.Tensor]) -> None:
+    for t in tensors:
+        if t is not None:
+            if not t.is_cuda:
+                raise ValueError("l2kv works on device tensors only")
+            if not t.is_contiguous():
+                raise ValueError("l2kv needs contiguous tensors")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream: Optional[torch.cuda.Stream]):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+# ------------------------------------------------------------ host helpers
+def l2kv_keep_count(T: int, keep_ratio: float) -> int:
+    return int(lib().l2kv_keep_count(int(T), float(keep_ratio)))
+
+
+def l2kv_select_workspace_bytes(n_heads: int, T: int) -> int:
+    return int(lib().l2kv_select_workspace_bytes(int(n_heads), int(T)))
+
+
+def l2kv_decode_workspace_bytes(B: int, Hq: int, kv_len: int, D: int) -> int:
+    return int(lib().l2kv_decode_workspace_bytes(int(B), int(Hq), int(kv_len), int(D)))
+
+
+def l2kv_decode_max_splits(kv_len: int) -> int:
+    return int(lib().l2kv_decode_max_splits(int(kv_len)))
+
+
+def l2kv_version() -> int:
+    return int(lib().l2kv_version())
+
+
+def _heads(x: torch.Tensor):
+    """[..., T, D] -> (n_heads, T, D)."""
+    *lead, T, D = x.shape
+    n = 1
+    for v in lead:
+        n *= v
+    return n, T, D
+
+
+# ------------------------------------------------------------ device calls
+def l2kv_norms(K: torch.Tensor, norms: torch.Tensor, stream=None) -> None:
+    """K ``[..., T, D]`` (f32/bf16) -> norms ``[..., T]`` float32 (pre-allocated)."""
+    _dev(K, norms)
+    n, T, D = _heads(K)
+    assert norms.dtype == torch.float32 and norms.numel() == n * T
+    _check("l2kv_norms", lib().l2kv_norms(_ptr(K), _dtype_code(K), n, T, D, T * D, _ptr(norms),
+                                          _stream(stream)))
+
+
+def l2kv_select(norms: torch.Tensor, keep_ratio: float, kept_idx: torch.Tensor,
+                kept_count: Optional[torch.Tensor], workspace: torch.Tensor, stream=None) -> None:
+    """norms ``[..., T]`` -> kept_idx ``[..., k]`` int32, k = l2kv_keep_count(T, keep_ratio)."""
+    _dev(norms, kept_idx, kept_count, workspace)
+    T = norms.shape[-1]
+    n = norms.numel() // T
+    assert norms.dtype == torch.float32 and kept_idx.dtype == torch.int32
+    _check("l2kv_select", lib().l2kv_select(_ptr(norms), n, T, float(keep_ratio), _ptr(kept_idx),
+                                            _ptr(kept_count), _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(),
+                                            _stream(stream)))
+
+
+def l2kv_select_k(norms: torch.Tensor, k: int, mode: int, kept_idx: torch.Tensor,
+                  kept_count: Optional[torch.Tensor], workspace: torch.Tensor, stream=None) -> None:
+    _dev(norms, kept_idx, kept_count, workspace)
+    T = norms.shape[-1]
+    n = norms.numel() // T
+    assert norms.dtype == torch.float32 and kept_idx.dtype == torch.int32
+    _check("l2kv_select_k", lib().l2kv_select_k(_ptr(norms), n, T, int(k), int(mode), _ptr(kept_idx),
+                                                _ptr(kept_count), _ptr(workspace),
+                                                workspace.numel() * workspace.element_size(),
+                                                _stream(stream)))
+
+
+def l2kv_compact(K: torch.Tensor, V: Optional[torch.Tensor], kept_idx: torch.Tensor,
+                 Kc: torch.Tensor, Vc: Optional[torch.Tensor], stream=None) -> None:
+    """Gather rows kept_idx ``[..., k]`` of K, V ``[..., T, D]`` into Kc, Vc ``[..., k, D]``."""
+    _dev(K, V, kept_idx, Kc, Vc)
+    n, T, D = _heads(K)
+    k = kept_idx.shape[-1]
+    assert kept_idx.dtype == torch.int32 and kept_idx.numel() == n * k
+    assert Kc.dtype == K.dtype and Kc.numel() == n * k * D
+    if V is not None:
+        assert V.shape == K.shape and V.dtype == K.dtype and Vc is not None and Vc.numel() == Kc.numel()
+    _check("l2kv_compact", lib().l2kv_compact(_ptr(K), _ptr(V), _dtype_code(K), _ptr(kept_idx), n, T, k,
+                                              D, T * D, _ptr(Kc), _ptr(Vc), _stream(stream)))
+
+
+def l2kv_decode_attn(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, O: torch.Tensor,
+                     workspace: torch.Tensor, scale: float = 0.0, stream=None) -> None:
+    """Q ``[B, Hq, D]``, Kc/Vc ``[B, Hkv, n, D]`` -> O ``[B, Hq, D]`` float32."""
+    l2kv_decode_attn_splits(Q, Kc, Vc, O, workspace, scale=scale, n_splits=None, stream=stream)
+
+
+def l2kv_decode_attn_splits(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, O: torch.Tensor,
+                            workspace: torch.Tensor, scale: float = 0.0,
+                            n_splits: Optional[int] = 0, stream=None) -> None:
+    _dev(Q, Kc, Vc, O, workspace)
+    B, Hq, D = Q.shape
+    Bk, Hkv, n, Dk = Kc.shape
+    assert (Bk, Dk) == (B, D) and Vc.shape == Kc.shape and Kc.dtype == Q.dtype == Vc.dtype
+    assert O.dtype == torch.float32 and O.numel() == B * Hq * D
+    ws_bytes = workspace.numel() * workspace.element_size()
+    if n_splits is None:
+        st = lib().l2kv_decode_attn(_ptr(Q), _ptr(Kc), _ptr(Vc), _dtype_code(Q), B, Hq, Hkv, n, D,
+                                    n * D, float(scale), _ptr(O), _ptr(workspace), ws_bytes,
+                                    _stream(stream))
+        _check("l2kv_decode_attn", st)
+    else:
+        st = lib().l2kv_decode_attn_splits(_ptr(Q), _ptr(Kc), _ptr(Vc), _dtype_code(Q), B, Hq, Hkv, n,
+                                           D, n * D, float(scale), int(n_splits), _ptr(O),
+                                           _ptr(workspace), ws_bytes, _stream(stream))
+        _check("l2kv_decode_attn_splits", st)

@@ -1,0 +1,177 @@
+// C ABI of libl2kv.so: argument validation on the host, then the launchers.
+// Nothing here allocates, synchronises or touches device memory; a negative
+// status means no kernel was enqueued.
+#include <atomic>
+#include <cmath>
+
+#include "l2kv_host.hpp"
+
+namespace l2kv {
+
+int device_compute_units() {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> cached[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    int cu = cached[dev].load(std::memory_order_relaxed);
+    if (cu > 0) return cu;
+    if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0) {
+        (void)hipGetLastError();
+        cu = 256;
+    }
+    cached[dev].store(cu, std::memory_order_relaxed);
+    return cu;
+}
+
+namespace {
+
+inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+inline bool dtype_ok(l2kv_dtype dt) { return dt == L2KV_F32 || dt == L2KV_BF16; }
+inline int elem_bytes(l2kv_dtype dt) { return dt == L2KV_F32 ? 4 : 2; }
+inline bool dim_ok(int32_t D) { return D == 64 || D == 128; }
+constexpr int64_t kMaxTokens = 0x7fffffffLL;          // token indices are int32
+constexpr int64_t kMaxHeads = 0x7fffffffLL;
+
+// Shared checks of a strided [n_heads][T][D] tensor description.
+l2kv_status check_cache(l2kv_dtype dt, int64_t n_heads, int64_t T, int32_t D, int64_t head_stride) {
+    if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
+    if (n_heads <= 0 || n_heads > kMaxHeads || T <= 0 || T > kMaxTokens || !dim_ok(D))
+        return L2KV_ERR_SHAPE;
+    if (head_stride < T * (int64_t)D) return L2KV_ERR_SHAPE;
+    if ((head_stride * elem_bytes(dt)) % 16 != 0) return L2KV_ERR_ALIGN;
+    return L2KV_OK;
+}
+
+}  // namespace
+}  // namespace l2kv
+
+using namespace l2kv;
+
+extern "C" {
+
+int64_t l2kv_keep_count(int64_t T, double keep_ratio) {
+    if (T <= 0 || !(keep_ratio > 0.0) || !(keep_ratio <= 1.0)) return 0;
+    const double x = keep_ratio * static_cast<double>(T);
+    const double whole = std::nearbyint(x);
+    const double slack = 1e-9 * (x > 1.0 ? x : 1.0);
+    double kd = std::fabs(x - whole) <= slack ? whole : std::ceil(x);
+    if (kd < 1.0) kd = 1.0;
+    if (kd > static_cast<double>(T)) kd = static_cast<double>(T);
+    return static_cast<int64_t>(kd);
+}
+
+l2kv_status l2kv_norms(const void* K, l2kv_dtype dt, int64_t n_heads, int64_t T, int32_t D,
+                       int64_t head_stride, float* norms, void* stream) {
+    if (K == nullptr || norms == nullptr) return L2KV_ERR_NULL;
+    if (l2kv_status st = check_cache(dt, n_heads, T, D, head_stride); st != L2KV_OK) return st;
+    if (!aligned(K, 16) || !aligned(norms, 4)) return L2KV_ERR_ALIGN;
+    return norms_dispatch(K, dt, n_heads, T, D, head_stride, norms, static_cast<hipStream_t>(stream));
+}
+
+size_t l2kv_select_workspace_bytes(int64_t n_heads, int64_t T) {
+    // The current kernels keep all selection state in registers and LDS; a
+    // small fixed size is reported so callers exercise the argument.
+    (void)n_heads;
+    (void)T;
+    return 256;
+}
+
+l2kv_status l2kv_select_k(const float* norms, int64_t n_heads, int64_t T, int64_t k, l2kv_mode mode,
+                          int32_t* kept_idx, int32_t* kept_count, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+    if (norms == nullptr || kept_idx == nullptr) return L2KV_ERR_NULL;
+    if (n_heads <= 0 || n_heads > kMaxHeads || T <= 0 || T > kMaxTokens) return L2KV_ERR_SHAPE;
+    if (k <= 0 || k > T) return L2KV_ERR_SHAPE;
+    if (mode != L2KV_KEEP_LOWEST && mode != L2KV_KEEP_HIGHEST) return L2KV_ERR_SHAPE;
+    if (workspace == nullptr || workspace_bytes < l2kv_select_workspace_bytes(n_heads, T))
+        return L2KV_ERR_WORKSPACE;
+    if (!aligned(norms, 4) || !aligned(kept_idx, 4) || !aligned(kept_count, 4) || !aligned(workspace, 16))
+        return L2KV_ERR_ALIGN;
+    return select_dispatch(norms, n_heads, T, k, mode, kept_idx, kept_count, workspace,
+                           static_cast<hipStream_t>(stream));
+}
+
+l2kv_status l2kv_select(const float* norms, int64_t n_heads, int64_t T, double keep_ratio,
+                        int32_t* kept_idx, int32_t* kept_count, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+    if (norms == nullptr || kept_idx == nullptr) return L2KV_ERR_NULL;
+    if (n_heads <= 0 || n_heads > kMaxHeads || T <= 0 || T > kMaxTokens) return L2KV_ERR_SHAPE;
+    if (!(keep_ratio > 0.0) || !(keep_ratio <= 1.0)) return L2KV_ERR_RATIO;   // also rejects NaN
+    return l2kv_select_k(norms, n_heads, T, l2kv_keep_count(T, keep_ratio), L2KV_KEEP_LOWEST,
+                         kept_idx, kept_count, workspace, workspace_bytes, stream);
+}
+
+l2kv_status l2kv_compact(const void* K, const void* V, l2kv_dtype dt, const int32_t* kept_idx,
+                         int64_t n_heads, int64_t T, int64_t k, int32_t D, int64_t head_stride,
+                         void* Kc, void* Vc, void* stream) {
+    if (K == nullptr || Kc == nullptr || kept_idx == nullptr) return L2KV_ERR_NULL;
+    if ((V == nullptr) != (Vc == nullptr)) return L2KV_ERR_NULL;
+    if (l2kv_status st = check_cache(dt, n_heads, T, D, head_stride); st != L2KV_OK) return st;
+    if (k <= 0 || k > T) return L2KV_ERR_SHAPE;
+    if (!aligned(K, 16) || !aligned(V, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(kept_idx, 4))
+        return L2KV_ERR_ALIGN;
+    return compact_dispatch(K, V, dt, kept_idx, n_heads, T, k, D, head_stride, Kc, Vc,
+                            static_cast<hipStream_t>(stream));
+}
+
+int32_t l2kv_decode_max_splits(int64_t kv_len) { return decode_max_splits(kv_len); }
+
+size_t l2kv_decode_workspace_bytes(int32_t B, int32_t Hq, int64_t kv_len, int32_t D) {
+    if (B <= 0 || Hq <= 0 || kv_len <= 0 || D <= 0) return 0;
+    return static_cast<size_t>(B) * static_cast<size_t>(Hq) *
+           static_cast<size_t>(decode_max_splits(kv_len)) * static_cast<size_t>(D + 2) * sizeof(float);
+}
+
+l2kv_status l2kv_decode_attn_splits(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt,
+                                    int32_t B, int32_t Hq, int32_t Hkv, int64_t kv_len, int32_t D,
+                                    int64_t kv_head_stride, float scale, int32_t n_splits, float* O,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+    if (Q == nullptr || Kc == nullptr || Vc == nullptr || O == nullptr) return L2KV_ERR_NULL;
+    if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || kv_len <= 0 || kv_len > kMaxTokens || !dim_ok(D))
+        return L2KV_ERR_SHAPE;
+    if (Hq % Hkv != 0 || Hq / Hkv > 8) return L2KV_ERR_SHAPE;
+    if (static_cast<int64_t>(B) * Hkv > 65535 || static_cast<int64_t>(B) * Hq > 0x7fffffffLL)
+        return L2KV_ERR_SHAPE;
+    if (kv_head_stride < kv_len * static_cast<int64_t>(D)) return L2KV_ERR_SHAPE;
+    if (n_splits < 0 || n_splits > decode_max_splits(kv_len)) return L2KV_ERR_SHAPE;
+    if (!std::isfinite(scale)) return L2KV_ERR_SHAPE;
+    if (workspace == nullptr || workspace_bytes < l2kv_decode_workspace_bytes(B, Hq, kv_len, D))
+        return L2KV_ERR_WORKSPACE;
+    if ((kv_head_stride * elem_bytes(dt)) % 16 != 0) return L2KV_ERR_ALIGN;
+    if (!aligned(Q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(O, 4) || !aligned(workspace, 16))
+        return L2KV_ERR_ALIGN;
+    const float s = scale > 0.f ? scale : 1.0f / std::sqrt(static_cast<float>(D));
+    const DecodePlan plan = decode_plan(B, Hkv, kv_len, n_splits);
+    return decode_dispatch(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, s, plan, O,
+                           static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+l2kv_status l2kv_decode_attn(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt, int32_t B,
+                             int32_t Hq, int32_t Hkv, int64_t kv_len, int32_t D,
+                             int64_t kv_head_stride, float scale, float* O, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    return l2kv_decode_attn_splits(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, scale, 0, O,
+                                   workspace, workspace_bytes, stream);
+}
+
+const char* l2kv_status_string(l2kv_status s) {
+    switch (s) {
+        case L2KV_OK: return "ok";
+        case L2KV_ERR_NULL: return "a required pointer is NULL";
+        case L2KV_ERR_SHAPE: return "unsupported or inconsistent size";
+        case L2KV_ERR_DTYPE: return "unsupported dtype";
+        case L2KV_ERR_RATIO: return "keep_ratio must be in (0, 1]";
+        case L2KV_ERR_WORKSPACE: return "workspace missing or too small";
+        case L2KV_ERR_ALIGN: return "pointer or stride alignment violated";
+        case L2KV_ERR_LAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+int32_t l2kv_version(void) { return 100; }
+
+}  // extern "C"

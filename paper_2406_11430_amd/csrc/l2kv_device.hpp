@@ -1,0 +1,108 @@
+// Device-side helpers shared by the l2kv kernels (gfx950, wave64).
+//
+// Layout convention used by every streaming kernel: a K or V row is split over
+// a "row group" of 16 consecutive lanes, lane c of the group owning the c-th
+// sixteenth of the row (D/16 consecutive elements).  A wavefront therefore
+// holds 4 rows per load instruction, and a DPP row (16 lanes) is exactly one
+// cache row, so per-row reductions never leave the DPP row.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace l2kv {
+
+constexpr int kWaveSize = 64;
+constexpr int kRowLanes = 16;   // lanes cooperating on one cache row
+constexpr int kRowsPerWaveLoad = kWaveSize / kRowLanes;
+
+// DPP control words (cross-lane operand swizzles inside a 16-lane row).
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // lane i <- lane 7-i within 8 lanes
+constexpr int kDppMirror = 0x140;     // lane i <- lane 15-i within 16 lanes
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_read(float v) {
+    int iv = __builtin_bit_cast(int, v);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(iv, iv, CTRL, 0xf, 0xf, false));
+}
+
+// Sum over the 16 lanes of a row group as a balanced binary tree over
+// neighbouring lanes: (0+1),(2+3),... then pairs of those, etc.  After the two
+// quad steps every lane of a quad holds the same value, so the mirror swizzles
+// pair quad q with quad q^1 and then half h with half h^1.  IEEE addition is
+// commutative, hence all 16 lanes end with the identical bit pattern.
+__device__ __forceinline__ float row16_tree_sum(float p) {
+    p = p + dpp_read<kDppXor1>(p);
+    p = p + dpp_read<kDppXor2>(p);
+    p = p + dpp_read<kDppHalfMirror>(p);
+    p = p + dpp_read<kDppMirror>(p);
+    return p;
+}
+
+// bf16 -> fp32 widening is a 16-bit shift (exact).
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
+
+// A lane's slice of a row as W 32-bit words (W = 2, 4 or 8).
+template <int W> struct Words { uint32_t w[W]; };
+
+template <int W>
+__device__ __forceinline__ Words<W> load_words(const void* p) {
+    Words<W> r;
+    if constexpr (W == 2) {
+        uint2 v = *reinterpret_cast<const uint2*>(p);
+        r.w[0] = v.x; r.w[1] = v.y;
+    } else {
+        static_assert(W % 4 == 0, "slice must be 8 bytes or a multiple of 16");
+#pragma unroll
+        for (int i = 0; i < W / 4; ++i) {
+            uint4 v = reinterpret_cast<const uint4*>(p)[i];
+            r.w[4 * i + 0] = v.x; r.w[4 * i + 1] = v.y;
+            r.w[4 * i + 2] = v.z; r.w[4 * i + 3] = v.w;
+        }
+    }
+    return r;
+}
+
+template <int W>
+__device__ __forceinline__ void store_words(void* p, const Words<W>& r) {
+    if constexpr (W == 2) {
+        *reinterpret_cast<uint2*>(p) = make_uint2(r.w[0], r.w[1]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < W / 4; ++i)
+            reinterpret_cast<uint4*>(p)[i] =
+                make_uint4(r.w[4 * i + 0], r.w[4 * i + 1], r.w[4 * i + 2], r.w[4 * i + 3]);
+    }
+}
+
+// Element type tags.
+struct F32 { static constexpr int kBytes = 4; };
+struct BF16 { static constexpr int kBytes = 2; };
+
+// Slice geometry for element type E and head_dim D.
+template <typename E, int D> struct Slice {
+    static constexpr int kElems = D / kRowLanes;               // elements per lane
+    static constexpr int kWords = kElems * E::kBytes / 4;      // 32-bit words per lane
+    static constexpr int kBytes = kElems * E::kBytes;          // bytes per lane
+    static constexpr int kRowBytes = D * E::kBytes;
+};
+
+// Widen a lane's slice to fp32 values in element order.
+template <typename E, int D>
+__device__ __forceinline__ void widen(const Words<Slice<E, D>::kWords>& r, float (&x)[Slice<E, D>::kElems]) {
+    if constexpr (E::kBytes == 4) {
+#pragma unroll
+        for (int i = 0; i < Slice<E, D>::kElems; ++i) x[i] = __builtin_bit_cast(float, r.w[i]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < Slice<E, D>::kWords; ++i) {
+            x[2 * i] = bf16_lo(r.w[i]);
+            x[2 * i + 1] = bf16_hi(r.w[i]);
+        }
+    }
+}
+
+}  // namespace l2kv

@@ -1,0 +1,45 @@
+// Host-side glue between the C ABI (api.hip) and the per-kernel launchers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/l2kv.h"
+
+namespace l2kv {
+
+// Status of the launch just enqueued on the calling thread.
+inline l2kv_status launch_status() {
+    return hipGetLastError() == hipSuccess ? L2KV_OK : L2KV_ERR_LAUNCH;
+}
+
+// Compute units of the current device (cached per device id).
+int device_compute_units();
+
+l2kv_status norms_dispatch(const void* K, l2kv_dtype dt, int64_t n_heads, int64_t T, int32_t D,
+                           int64_t head_stride, float* norms, hipStream_t stream);
+
+l2kv_status select_dispatch(const float* norms, int64_t n_heads, int64_t T, int64_t k,
+                            l2kv_mode mode, int32_t* kept_idx, int32_t* kept_count,
+                            void* workspace, hipStream_t stream);
+
+l2kv_status compact_dispatch(const void* K, const void* V, l2kv_dtype dt, const int32_t* kept_idx,
+                             int64_t n_heads, int64_t T, int64_t k, int32_t D, int64_t head_stride,
+                             void* Kc, void* Vc, hipStream_t stream);
+
+// Row-range decomposition of decode attention over kv_len rows.
+struct DecodePlan {
+    int32_t n_splits;        // row ranges per KV head actually launched
+    int64_t rows_per_split;  // multiple of the block's row tile
+};
+constexpr int kDecodeMaxSplits = 256;
+constexpr int kDecodeRowTile = 64;   // rows one workgroup consumes per step (4 waves x 16)
+int32_t decode_max_splits(int64_t kv_len);
+DecodePlan decode_plan(int32_t B, int32_t Hkv, int64_t kv_len, int32_t requested_splits);
+
+l2kv_status decode_dispatch(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt, int32_t B,
+                            int32_t Hq, int32_t Hkv, int64_t kv_len, int32_t D,
+                            int64_t kv_head_stride, float scale, const DecodePlan& plan, float* O,
+                            float* workspace, hipStream_t stream);
+
+}  // namespace l2kv

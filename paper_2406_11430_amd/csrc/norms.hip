@@ -1,0 +1,85 @@
+// l2kv_norms: squared L2 norm of every cached key row (the quantity the
+// eviction rule of arXiv 2406.11430, Sec. 1 / Sec. 3, ranks by).
+//
+// Pure HBM read stream of K.  16 lanes share a row (one 16-byte load each for
+// the 256-byte rows of the supported shapes), a wavefront covers 4 rows per
+// load instruction, and every lane issues kUnroll independent loads before the
+// first use so enough bytes are in flight.  The per-row sum follows the
+// library's fixed order: per-lane chunk left to right, then the balanced tree
+// of row16_tree_sum.  Contraction to FMA is switched off so fp32 inputs round
+// product and sum separately, like the stated order says.
+#include "l2kv_device.hpp"
+#include "l2kv_host.hpp"
+
+namespace l2kv {
+
+constexpr int kNormThreads = 256;
+constexpr int kNormWaves = kNormThreads / kWaveSize;
+constexpr int kNormUnroll = 8;                                   // rows per row group
+constexpr int kNormRowsPerBlock = kNormWaves * kRowsPerWaveLoad * kNormUnroll;  // 128
+
+template <typename E, int D>
+__global__ __launch_bounds__(kNormThreads)
+void norms_kernel(const char* __restrict__ K, int64_t T, int64_t head_stride_bytes,
+                  int64_t blocks_per_head, float* __restrict__ norms) {
+#pragma clang fp contract(off)
+    using S = Slice<E, D>;
+    const int64_t head = blockIdx.x / blocks_per_head;
+    const int64_t chunk = blockIdx.x % blocks_per_head;
+    const int lane = threadIdx.x % kWaveSize;
+    const int wave = threadIdx.x / kWaveSize;
+    const int c = lane % kRowLanes;       // slice within the row
+    const int rg = lane / kRowLanes;      // row group within the wave
+
+    // Row group (wave, rg) owns kNormUnroll consecutive rows.
+    const int64_t first = chunk * kNormRowsPerBlock + (wave * kRowsPerWaveLoad + rg) * kNormUnroll;
+    const char* head_base = K + head * head_stride_bytes;
+
+    Words<S::kWords> raw[kNormUnroll];
+#pragma unroll
+    for (int u = 0; u < kNormUnroll; ++u) {
+        int64_t row = first + u;
+        row = row < T ? row : T - 1;      // tail: re-read the last row, result unused
+        raw[u] = load_words<S::kWords>(head_base + row * S::kRowBytes + c * S::kBytes);
+    }
+
+    float mine = 0.f;
+#pragma unroll
+    for (int u = 0; u < kNormUnroll; ++u) {
+        float x[S::kElems];
+        widen<E, D>(raw[u], x);
+        float acc = x[0] * x[0];
+#pragma unroll
+        for (int e = 1; e < S::kElems; ++e) {
+            float sq = x[e] * x[e];
+            acc = acc + sq;
+        }
+        float total = row16_tree_sum(acc);
+        mine = (c == u) ? total : mine;   // lane c keeps the sum of row u
+    }
+    const int64_t row = first + c;
+    if (c < kNormUnroll && row < T) norms[head * T + row] = mine;
+}
+
+template <typename E, int D>
+static l2kv_status launch_norms(const void* K, int64_t n_heads, int64_t T, int64_t head_stride,
+                                float* norms, hipStream_t stream) {
+    const int64_t bph = (T + kNormRowsPerBlock - 1) / kNormRowsPerBlock;
+    const int64_t blocks = bph * n_heads;
+    if (blocks > 0x7fffffffLL) return L2KV_ERR_SHAPE;
+    hipLaunchKernelGGL((norms_kernel<E, D>), dim3((unsigned)blocks), dim3(kNormThreads), 0, stream,
+                       static_cast<const char*>(K), T, head_stride * (int64_t)E::kBytes, bph, norms);
+    return launch_status();
+}
+
+l2kv_status norms_dispatch(const void* K, l2kv_dtype dt, int64_t n_heads, int64_t T, int32_t D,
+                           int64_t head_stride, float* norms, hipStream_t stream) {
+    if (dt == L2KV_F32) {
+        return D == 64 ? launch_norms<F32, 64>(K, n_heads, T, head_stride, norms, stream)
+                       : launch_norms<F32, 128>(K, n_heads, T, head_stride, norms, stream);
+    }
+    return D == 64 ? launch_norms<BF16, 64>(K, n_heads, T, head_stride, norms, stream)
+                   : launch_norms<BF16, 128>(K, n_heads, T, head_stride, norms, stream);
+}
+
+}  // namespace l2kv

@@ -1,0 +1,163 @@
+// l2kv_select: per head, the k positions that come first in the total order
+// (bit pattern of the fp32 squared norm, token index), written in ascending
+// token order.  This is the eviction rule of arXiv 2406.11430 (Sec. 1: keep
+// the lowest-norm keys; Eq. 5: exactly m pairs dropped per layer and head)
+// with ties resolved towards the lower token index.
+//
+// One workgroup of 1024 lanes per head.  The keys (norm bits, complemented for
+// the keep-highest control) sit in registers -- 32 per lane covers 32k tokens
+// -- so nothing is re-read from memory.  The k-th smallest key tau is found
+// exactly by a 32-step binary search on its bits: step b counts the keys below
+// (prefix | 1<<b) with wave ballots + popcounts (scalar unit), one LDS atomic
+// per wave and one barrier.  No histogram, no data-dependent contention.
+// The emit is ordered: every wave owns a contiguous token range, so a prefix
+// over the 16 wave totals plus a running ballot prefix gives each kept token
+// its output slot; keys equal to tau are admitted in token order until the
+// budget k is met.
+#include "l2kv_device.hpp"
+#include "l2kv_host.hpp"
+
+namespace l2kv {
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / kWaveSize;   // 16
+constexpr int kSelMaxRegKeys = 32;                   // keys per lane held in registers
+
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// E > 0: keys of the head fit E per lane and are cached in registers.
+// E == 0: streaming variant, keys are re-read from memory (L2) in every pass.
+template <int E>
+__global__ __launch_bounds__(kSelThreads)
+void select_kernel(const uint32_t* __restrict__ norm_bits, int64_t T, uint32_t k, uint32_t flip,
+                   int32_t* __restrict__ kept_idx, int32_t* __restrict__ kept_count) {
+    constexpr bool kInRegs = E > 0;
+    __shared__ uint32_t s_count[32];
+    __shared__ uint32_t s_lt[kSelWaves];
+    __shared__ uint32_t s_eq[kSelWaves];
+
+    const int64_t head = blockIdx.x;
+    const int lane = threadIdx.x % kWaveSize;
+    const int wave = threadIdx.x / kWaveSize;
+    const uint32_t* src = norm_bits + head * T;
+
+    // Wave w owns tokens [w*span, (w+1)*span), span a multiple of 64; iteration
+    // e of lane l looks at token w*span + e*64 + l.
+    const int64_t iters = kInRegs ? E : (((T + kSelWaves - 1) / kSelWaves + kWaveSize - 1) / kWaveSize);
+    const int64_t span = iters * kWaveSize;
+    const int64_t t0 = wave * span + lane;
+
+    auto fetch = [&](int64_t e) -> uint32_t {
+        const int64_t t = t0 + e * kWaveSize;
+        return t < T ? (src[t] ^ flip) : 0xffffffffu;   // padding can never be "below"
+    };
+
+    uint32_t regs[kInRegs ? E : 1];
+    if constexpr (kInRegs) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) regs[e] = fetch(e);
+    }
+    if (threadIdx.x < 32) s_count[threadIdx.x] = 0;
+    __syncthreads();
+
+    // ---- k-th smallest key by binary search on its bits (MSB first) -------
+    uint32_t prefix = 0;     // tau so far
+    uint32_t less = 0;       // number of keys < prefix
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t cand = prefix | (1u << bit);
+        uint32_t cnt = 0;
+        if constexpr (kInRegs) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) cnt += __popcll(__ballot(regs[e] < cand));
+        } else {
+            for (int64_t e = 0; e < iters; ++e) cnt += __popcll(__ballot(fetch(e) < cand));
+        }
+        if (lane == 0 && cnt) atomicAdd(&s_count[bit], cnt);
+        __syncthreads();
+        const uint32_t below = s_count[bit];
+        if (below < k) {     // the k-th smallest is >= cand
+            prefix = cand;
+            less = below;
+        }
+    }
+    const uint32_t tau = prefix;
+    const uint32_t need_eq = k - less;   // >= 1 keys equal to tau are kept, lowest tokens first
+
+    // ---- per-wave totals, then ordered emit ---------------------------------
+    uint32_t lt_w = 0, eq_w = 0;
+    auto tally = [&](uint32_t key, int64_t e) {
+        const bool valid = (t0 + e * kWaveSize) < T;
+        lt_w += __popcll(__ballot(key < tau));
+        eq_w += __popcll(__ballot(valid && key == tau));
+    };
+    if constexpr (kInRegs) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) tally(regs[e], e);
+    } else {
+        for (int64_t e = 0; e < iters; ++e) tally(fetch(e), e);
+    }
+    if (lane == 0) {
+        s_lt[wave] = lt_w;
+        s_eq[wave] = eq_w;
+    }
+    __syncthreads();
+    uint32_t lt_before = 0, eq_before = 0;
+    for (int w = 0; w < wave; ++w) {
+        lt_before += s_lt[w];
+        eq_before += s_eq[w];
+    }
+    uint32_t out_base = lt_before + (eq_before < need_eq ? eq_before : need_eq);
+    uint32_t eq_base = eq_before;
+    int32_t* out = kept_idx + head * (int64_t)k;
+
+    auto emit = [&](uint32_t key, int64_t e) {
+        const int64_t t = t0 + e * kWaveSize;
+        const bool valid = t < T;
+        const bool is_lt = key < tau;
+        const bool is_eq = valid && key == tau;
+        const uint64_t eq_mask = __ballot(is_eq);
+        const bool keep = is_lt || (is_eq && (eq_base + lanes_below(eq_mask)) < need_eq);
+        const uint64_t keep_mask = __ballot(keep);
+        if (keep) out[out_base + lanes_below(keep_mask)] = (int32_t)t;
+        out_base += __popcll(keep_mask);
+        eq_base += __popcll(eq_mask);
+    };
+    if constexpr (kInRegs) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) emit(regs[e], e);
+    } else {
+        for (int64_t e = 0; e < iters; ++e) emit(fetch(e), e);
+    }
+    if (kept_count != nullptr && threadIdx.x == 0) kept_count[head] = (int32_t)k;
+}
+
+template <int E>
+static void launch_select(const float* norms, int64_t n_heads, int64_t T, int64_t k, uint32_t flip,
+                          int32_t* kept_idx, int32_t* kept_count, hipStream_t stream) {
+    hipLaunchKernelGGL((select_kernel<E>), dim3((unsigned)n_heads), dim3(kSelThreads), 0, stream,
+                       reinterpret_cast<const uint32_t*>(norms), T, (uint32_t)k, flip, kept_idx,
+                       kept_count);
+}
+
+l2kv_status select_dispatch(const float* norms, int64_t n_heads, int64_t T, int64_t k,
+                            l2kv_mode mode, int32_t* kept_idx, int32_t* kept_count,
+                            void* workspace, hipStream_t stream) {
+    (void)workspace;
+    if (n_heads > 0x7fffffffLL) return L2KV_ERR_SHAPE;
+    const uint32_t flip = mode == L2KV_KEEP_HIGHEST ? 0xffffffffu : 0u;
+    const int64_t per_lane = (T + kSelThreads - 1) / kSelThreads;
+    if (per_lane <= 1)       launch_select<1>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
+    else if (per_lane <= 2)  launch_select<2>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
+    else if (per_lane <= 4)  launch_select<4>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
+    else if (per_lane <= 8)  launch_select<8>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
+    else if (per_lane <= 16) launch_select<16>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
+    else if (per_lane <= kSelMaxRegKeys)
+        launch_select<32>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
+    else
+        launch_select<0>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
+    return launch_status();
+}
+
+}  // namespace l2kv

@@ -1,0 +1,258 @@
+#!/usr/bin/env python3
+"""Benchmark of the L2-norm KV-cache compression hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one synthetic batch of the
+32k-context Llama-3-8B-shaped GQA workload (config C3): compress every layer's
+cache once (key norms -> lowest-norm selection -> K/V compaction), then run 64
+decode steps of single-query GQA attention over the compacted cache of all 32
+layers.  Inputs are resident in HBM before the timed region starts.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3]
+
+Prints ONE JSON line: whole-path effective HBM GB/s (algorithmic bytes / wall
+time), microseconds per decode step, the roofline of the dominant kernel
+(decode attention) from HIP events on the launch stream, and the CPU oracle
+timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import paper_2406_11430_amd as l2kv            # noqa: E402
+from paper_2406_11430_amd import synth         # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
+
+
+# ----------------------------------------------------------------- byte model
+def compress_bytes_per_layer(cfg, k):
+    """Algorithmic HBM bytes of norms + select + compact for one layer."""
+    n = cfg.B * cfg.Hkv
+    row = cfg.D * cfg.elem_bytes
+    norms = n * cfg.T * row + n * cfg.T * 4            # read K, write norms
+    select = n * cfg.T * 4 + n * k * 4                 # read norms, write indices
+    compact = n * k * 4 + 2 * n * k * row + 2 * n * k * row   # indices + kept K,V rows in, rows out
+    return norms, select, compact
+
+
+def decode_bytes_per_layer(cfg, k):
+    """Algorithmic HBM bytes of one decode-attention call on one layer: Kc and
+    Vc once per KV head (shared by the query group), plus Q in and O out."""
+    n = cfg.B * cfg.Hkv
+    row = cfg.D * cfg.elem_bytes
+    return 2 * n * k * row + cfg.B * cfg.Hq * cfg.D * cfg.elem_bytes + cfg.B * cfg.Hq * cfg.D * 4
+
+
+# ------------------------------------------------------------------- workload
+class Workload:
+    def __init__(self, cfg, dev):
+        self.cfg, self.dev = cfg, dev
+        L, B, Hkv, Hq, D, T = cfg.L, cfg.B, cfg.Hkv, cfg.Hq, cfg.D, cfg.T
+        dt = synth.torch_dtype(cfg.dtype)
+        self.k = l2kv.l2kv_keep_count(T, cfg.keep_ratio)
+        self.K = torch.empty((L, B, Hkv, T, D), dtype=dt, device=dev)
+        self.V = torch.empty_like(self.K)
+        for layer in range(L):
+            Kl, Vl = synth.make_layer(cfg, layer, device=dev)
+            self.K[layer].copy_(Kl)
+            self.V[layer].copy_(Vl)
+            del Kl, Vl
+        self.Q = torch.empty((cfg.decode_steps, L, B, Hq, D), dtype=dt, device=dev)
+        for layer in range(L):
+            for step in range(cfg.decode_steps):
+                self.Q[step, layer].copy_(synth.make_query(cfg, layer, step, device=dev))
+        self.norms = torch.empty((L, B, Hkv, T), dtype=torch.float32, device=dev)
+        self.idx = torch.empty((L, B, Hkv, self.k), dtype=torch.int32, device=dev)
+        self.cnt = torch.empty((L, B, Hkv), dtype=torch.int32, device=dev)
+        self.Kc = torch.empty((L, B, Hkv, self.k, D), dtype=dt, device=dev)
+        self.Vc = torch.empty_like(self.Kc)
+        self.O = torch.empty((L, B, Hq, D), dtype=torch.float32, device=dev)
+        self.sel_ws = torch.zeros(l2kv.l2kv_select_workspace_bytes(L * B * Hkv, T),
+                                  dtype=torch.uint8, device=dev)
+        self.dec_ws = torch.zeros(l2kv.l2kv_decode_workspace_bytes(B, Hq, self.k, D),
+                                  dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+
+    # -- the hot path: every call below is one C-ABI entry point ---------------
+    def compress(self):
+        l2kv.l2kv_norms(self.K, self.norms)
+        l2kv.l2kv_select(self.norms, self.cfg.keep_ratio, self.idx, self.cnt, self.sel_ws)
+        l2kv.l2kv_compact(self.K, self.V, self.idx, self.Kc, self.Vc)
+
+    def decode_step(self, step):
+        for layer in range(self.cfg.L):
+            l2kv.l2kv_decode_attn(self.Q[step, layer], self.Kc[layer], self.Vc[layer],
+                                  self.O[layer], self.dec_ws)
+
+    def decode_all(self):
+        for step in range(self.cfg.decode_steps):
+            self.decode_step(step)
+
+    def step(self):
+        self.compress()
+        self.decode_all()
+
+
+# --------------------------------------------------------------- CPU baseline
+def cpu_baseline(w: Workload, layers, dec_steps):
+    """Time the CPU oracle, as it stands, on a bounded sample: the full
+    compression of `layers` layers plus `dec_steps` decode steps on each of
+    them.  Also compares the GPU results of the same sample with the oracle."""
+    import oracle
+    cfg = w.cfg
+    t_total = 0.0
+    bytes_total = 0
+    worst = 0.0
+    idx_equal = True
+    rows_equal = True
+    for layer in layers:
+        Kn = synth.as_numpy_bits(w.K[layer])
+        Vn = synth.as_numpy_bits(w.V[layer])
+        t0 = time.perf_counter()
+        n32, _, idx, Kc, Vc = oracle.compress(Kn, Vn, cfg.dtype, cfg.keep_ratio)
+        t_total += time.perf_counter() - t0
+        bytes_total += sum(compress_bytes_per_layer(cfg, w.k))
+        idx_equal &= bool(np.array_equal(idx, w.idx[layer].cpu().numpy()))
+        rows_equal &= bool(np.array_equal(Kc, synth.as_numpy_bits(w.Kc[layer])))
+        rows_equal &= bool(np.array_equal(Vc, synth.as_numpy_bits(w.Vc[layer])))
+        for step in range(dec_steps):
+            Qn = synth.as_numpy_bits(w.Q[step, layer])
+            t0 = time.perf_counter()
+            want = oracle.decode_attn(Qn, Kc, Vc, cfg.dtype)
+            t_total += time.perf_counter() - t0
+            bytes_total += decode_bytes_per_layer(cfg, w.k)
+            O = torch.empty((cfg.B, cfg.Hq, cfg.D), dtype=torch.float32, device=w.dev)
+            l2kv.l2kv_decode_attn(w.Q[step, layer], w.Kc[layer], w.Vc[layer], O, w.dec_ws)
+            worst = max(worst, float(np.abs(O.cpu().numpy() - want).max()))
+    return {
+        "value": bytes_total / t_total / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": "%s: full compress of layer(s) %s + %d decode step(s) on each; %.1f s of CPU time"
+                  % (cfg.name, list(layers), dec_steps, t_total),
+        "seconds": t_total,
+        "gpu_vs_oracle_on_sample": {"kept_idx_equal": idx_equal, "compacted_rows_equal": rows_equal,
+                                    "attn_max_abs_err": worst},
+    }
+
+
+# ----------------------------------------------------------------------- main
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="C3", choices=sorted(synth.CONFIGS))
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
+    ap.add_argument("--decode-steps", type=int, default=0, help="override decode steps (debug)")
+    ap.add_argument("--cpu-layers", type=int, default=4)
+    ap.add_argument("--cpu-decode-steps", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
+                 "(the path shards over KV heads with no exchange, but no multi-GPU "
+                 "code is part of this build)" % args.gpus)
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no HIP device visible")
+    l2kv.lib()                                   # fail loudly if the library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = synth.CONFIGS[args.workload]
+    overridden = False
+    if args.layers:
+        cfg, overridden = cfg.scaled(L=args.layers), True
+    if args.decode_steps:
+        cfg, overridden = cfg.scaled(decode_steps=args.decode_steps), True
+
+    w = Workload(cfg, dev)
+    k = w.k
+    nb, sb, cb = compress_bytes_per_layer(cfg, k)
+    comp_bytes = (nb + sb + cb) * cfg.L
+    dec_bytes_layer = decode_bytes_per_layer(cfg, k)
+    dec_bytes = dec_bytes_layer * cfg.L * cfg.decode_steps
+    step_bytes = comp_bytes + dec_bytes
+
+    for _ in range(args.warmup):
+        w.step()
+    torch.cuda.synchronize()
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)     # noqa: E731
+    marks = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        e = [ev() for _ in range(5)]
+        e[0].record()
+        l2kv.l2kv_norms(w.K, w.norms)
+        e[1].record()
+        l2kv.l2kv_select(w.norms, cfg.keep_ratio, w.idx, w.cnt, w.sel_ws)
+        e[2].record()
+        l2kv.l2kv_compact(w.K, w.V, w.idx, w.Kc, w.Vc)
+        e[3].record()
+        w.decode_all()
+        e[4].record()
+        marks.append(e)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in marks])  # [steps][4]
+    norms_ms, select_ms, compact_ms, decode_ms = ms.mean(axis=0)
+    ms_per_step = wall * 1e3 / args.steps
+    value = step_bytes / (wall / args.steps) / 1e9
+    n_decode_launch = cfg.L * cfg.decode_steps
+    us_per_layer_call = decode_ms * 1e3 / n_decode_launch
+    achieved = dec_bytes_layer / (us_per_layer_call * 1e-6) / 1e9
+
+    out = {
+        "metric": "compress+decode effective HBM GB/s",
+        "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {
+            "workload": cfg.name + (" (size overridden)" if overridden else ""),
+            "layers": cfg.L, "batch": cfg.B, "kv_heads": cfg.Hkv, "q_heads": cfg.Hq,
+            "head_dim": cfg.D, "cached_tokens": cfg.T, "keep_ratio": cfg.keep_ratio, "kept": k,
+            "decode_steps": cfg.decode_steps,
+            "step": "compress all layers once + decode_steps x layers decode-attention calls",
+        },
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "us_per_decode_step": round(decode_ms * 1e3 / cfg.decode_steps, 2),
+        "us_per_decode_layer": round(us_per_layer_call, 3),
+        "phases": {
+            "norms": {"ms": round(float(norms_ms), 4), "GBps": round(nb * cfg.L / norms_ms / 1e6, 1)},
+            "select": {"ms": round(float(select_ms), 4), "GBps": round(sb * cfg.L / select_ms / 1e6, 1)},
+            "compact": {"ms": round(float(compact_ms), 4), "GBps": round(cb * cfg.L / compact_ms / 1e6, 1)},
+            "compress": {"ms": round(float(norms_ms + select_ms + compact_ms), 4),
+                         "GBps": round(comp_bytes / (norms_ms + select_ms + compact_ms) / 1e6, 1)},
+            "decode": {"ms": round(float(decode_ms), 4), "GBps": round(dec_bytes / decode_ms / 1e6, 1)},
+        },
+        "roofline": {
+            "kernel": "decode attention (one l2kv_decode_attn call on one layer)",
+            "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+            "bytes_per_launch": dec_bytes_layer, "us_per_launch": round(us_per_layer_call, 3),
+            "timing": "HIP events on the launch stream around all %d calls of each step" % n_decode_launch,
+        },
+    }
+    if not args.no_cpu_baseline:
+        layers = list(range(min(args.cpu_layers, cfg.L)))
+        out["cpu_baseline"] = cpu_baseline(w, layers, min(args.cpu_decode_steps, cfg.decode_steps))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

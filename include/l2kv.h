@@ -140,8 +140,16 @@ l2kv_status l2kv_compact(const void* K, const void* V, l2kv_dtype dt,
  *   scale  : softmax scale; <= 0 selects 1/sqrt(D) (Eq. 2)
  *   O   out: [B][Hq][D] fp32
  *   workspace: l2kv_decode_workspace_bytes(B, Hq, kv_len, D) bytes,
- *              16-aligned, uninitialised; holds the split partials
- * Arithmetic: products and sums in fp32 (bf16 inputs widened exactly).
+ *              16-aligned.  It starts with one arrival counter per
+ *              (sequence, KV head) followed by the split partials.  The
+ *              counters must be ZERO before the first call that uses this
+ *              buffer (zero-fill the whole buffer once); every call leaves
+ *              them zero again, so the buffer can be reused call after call
+ *              for any shape it is large enough for.  Two calls that share a
+ *              workspace must not overlap in time.
+ * Arithmetic: fp32 accumulation throughout; for bf16 caches q.k is formed with
+ * the packed bf16 dot instruction (exact bf16 products, fp32 sum), for fp32
+ * caches with fp32 FMAs; softmax and the value sum are fp32.
  * Errors: NULL, SHAPE (Hq % Hkv != 0, Hq/Hkv > 8, kv_len <= 0, ...), DTYPE,
  * WORKSPACE, ALIGN, LAUNCH.
  */

@@ -36,8 +36,8 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found (set HIPCC or install ROCm)")
 
 
-def _compile(src: str, extra) -> str:
-    obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
+def _compile(src: str, extra, obj_dir: str = OBJ_DIR) -> str:
+    obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
     cmd = [hipcc(), *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass warns that it does not know the packed-fp32 feature: harmless
@@ -50,18 +50,19 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
-def build_library(extra_flags=(), jobs: int = 5) -> str:
-    """Compile every kernel source for gfx950 and link libl2kv.so."""
-    os.makedirs(OBJ_DIR, exist_ok=True)
+def build_library(extra_flags=(), jobs: int = 5, out: str = LIB_PATH, obj_dir: str = OBJ_DIR) -> str:
+    """Compile every kernel source for gfx950 and link the shared library
+    (libl2kv.so in the package unless `out` names another file)."""
+    os.makedirs(obj_dir, exist_ok=True)
     with ThreadPoolExecutor(max_workers=max(1, jobs)) as pool:
-        objs = list(pool.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
-    tmp = LIB_PATH + ".tmp.%d" % os.getpid()
+        objs = list(pool.map(lambda s: _compile(s, list(extra_flags), obj_dir), SOURCES))
+    tmp = out + ".tmp.%d" % os.getpid()
     cmd = [hipcc(), "--offload-arch=" + ARCH, "-shared", "-fPIC", *objs, "-o", tmp]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("link failed:\n" + res.stderr)
-    os.replace(tmp, LIB_PATH)
-    return LIB_PATH
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":

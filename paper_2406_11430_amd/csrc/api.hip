@@ -121,8 +121,10 @@ int32_t l2kv_decode_max_splits(int64_t kv_len) { return decode_max_splits(kv_len
 
 size_t l2kv_decode_workspace_bytes(int32_t B, int32_t Hq, int64_t kv_len, int32_t D) {
     if (B <= 0 || Hq <= 0 || kv_len <= 0 || D <= 0) return 0;
-    return static_cast<size_t>(B) * static_cast<size_t>(Hq) *
-           static_cast<size_t>(decode_max_splits(kv_len)) * static_cast<size_t>(D + 2) * sizeof(float);
+    // counters (at most one per query head: Hkv <= Hq) + split partials
+    return decode_counter_bytes(B, Hq) +
+           static_cast<size_t>(B) * static_cast<size_t>(Hq) *
+               static_cast<size_t>(decode_max_splits(kv_len)) * static_cast<size_t>(D + 2) * sizeof(float);
 }
 
 l2kv_status l2kv_decode_attn_splits(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt,
@@ -147,7 +149,7 @@ l2kv_status l2kv_decode_attn_splits(const void* Q, const void* Kc, const void* V
     const float s = scale > 0.f ? scale : 1.0f / std::sqrt(static_cast<float>(D));
     const DecodePlan plan = decode_plan(B, Hkv, kv_len, n_splits);
     return decode_dispatch(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, s, plan, O,
-                           static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
+                           workspace, static_cast<hipStream_t>(stream));
 }
 
 l2kv_status l2kv_decode_attn(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt, int32_t B,

@@ -7,16 +7,23 @@
 // Decomposition: grid (row range, sequence x KV head).  A workgroup of 4 waves
 // streams its row range once for all G = Hq/Hkv query heads of the KV head.
 // 16 lanes share a row (16 bytes each), a wave covers 16 rows of K and of V
-// per step (4 + 4 loads per lane) and prefetches the next step's rows before
-// computing on the current ones.  Every 16-lane row group runs its own online
-// softmax (running max m, denominator l, weighted value sum acc), so the only
-// cross-lane traffic in the loop is the 4-step DPP tree of each dot product.
-// At the end the 16 row groups of the workgroup are merged through LDS and one
-// partial (acc[D], m, l) per query head is written; a second small kernel
-// merges the partials of all row ranges and normalises.
+// per step (4 + 4 non-temporal loads per lane) and always has the next step's
+// rows in flight while it computes on the current ones (two register tiles,
+// ping-pong, no branch around the prefetch so the wait counters stay exact).
+// Every 16-lane row group runs its own online softmax (running max m,
+// denominator l, weighted value sum acc), so the only cross-lane traffic in
+// the loop is the 4-step DPP tree of each dot product.
 //
-// Scores are kept in the log2 domain: q is pre-multiplied by scale*log2(e) so
-// the exponentials are bare v_exp_f32.
+// bf16 caches: q.k uses the packed bf16 dot instruction with fp32 accumulate
+// (both operands are exact bf16 inputs); the softmax scale is applied to the
+// fp32 score afterwards.  fp32 caches use plain fp32 FMAs.
+//
+// At the end the 16 row groups of the workgroup are merged through LDS and one
+// partial (acc[D], m, l) per query head goes to the workspace.  The workgroup
+// that finishes last for its KV head (device-scope counter in the workspace)
+// merges the partials of all row ranges and writes O: one kernel per call.
+//
+// Scores are kept in the log2 domain so the exponentials are bare v_exp_f32.
 #include "l2kv_device.hpp"
 #include "l2kv_host.hpp"
 
@@ -33,45 +40,97 @@ static_assert(kDecWaves * kDecRowsPerStep == kDecodeRowTile, "row tile mismatch"
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+
+// Streaming (non-temporal) load of a lane's slice: the cache is read once per
+// call and must not displace anything in L2.
+template <int W>
+__device__ __forceinline__ Words<W> stream_words(const char* p) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    Words<W> r;
+    if constexpr (W == 2) {
+        u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+        r.w[0] = v.x; r.w[1] = v.y;
+    } else {
+#pragma unroll
+        for (int i = 0; i < W / 4; ++i) {
+                u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p) + i);
+            r.w[4 * i + 0] = v.x; r.w[4 * i + 1] = v.y; r.w[4 * i + 2] = v.z; r.w[4 * i + 3] = v.w;
+        }
+    }
+    return r;
+}
+
+// Device-scope (agent) relaxed store / load of one float.
+__device__ __forceinline__ void publish(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float fetch(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 template <typename E, int D>
 struct Tile {
     Words<Slice<E, D>::kWords> k[kDecLoads];
     Words<Slice<E, D>::kWords> v[kDecLoads];
 };
 
+// Loads the 16 rows [first_row, first_row+16) of K and V for this lane; all 16
+// rows must exist.  lane_off = rg * row_bytes + c * slice_bytes.
 template <typename E, int D>
 __device__ __forceinline__ void load_tile(Tile<E, D>& t, const char* Kh, const char* Vh,
-                                          int64_t first_row, int64_t last_valid, int rg, int c) {
+                                          int64_t first_row, int lane_off) {
     using S = Slice<E, D>;
+    const int64_t off = first_row * S::kRowBytes + lane_off;
 #pragma unroll
-    for (int u = 0; u < kDecLoads; ++u) {
-        int64_t row = first_row + u * kRowsPerWaveLoad + rg;
-        row = row < last_valid ? row : last_valid;       // tail rows re-read the last row; masked later
-        const int64_t off = row * S::kRowBytes + c * S::kBytes;
-        t.k[u] = load_words<S::kWords>(Kh + off);
-    }
+    for (int u = 0; u < kDecLoads; ++u)
+        t.k[u] = stream_words<S::kWords>(Kh + off + u * (kRowsPerWaveLoad * S::kRowBytes));
+#pragma unroll
+    for (int u = 0; u < kDecLoads; ++u)
+        t.v[u] = stream_words<S::kWords>(Vh + off + u * (kRowsPerWaveLoad * S::kRowBytes));
+}
+
+// Ragged last tile of a row range: rows past last_valid re-read row last_valid
+// (in bounds); the caller masks their scores.
+template <typename E, int D>
+__device__ __forceinline__ void load_tile_clamped(Tile<E, D>& t, const char* Kh, const char* Vh,
+                                                  int64_t first_row, int64_t last_valid, int rg, int c) {
+    using S = Slice<E, D>;
+    int64_t off[kDecLoads];
 #pragma unroll
     for (int u = 0; u < kDecLoads; ++u) {
         int64_t row = first_row + u * kRowsPerWaveLoad + rg;
         row = row < last_valid ? row : last_valid;
-        const int64_t off = row * S::kRowBytes + c * S::kBytes;
-        t.v[u] = load_words<S::kWords>(Vh + off);
+        off[u] = row * S::kRowBytes + c * S::kBytes;
     }
+#pragma unroll
+    for (int u = 0; u < kDecLoads; ++u) t.k[u] = stream_words<S::kWords>(Kh + off[u]);
+#pragma unroll
+    for (int u = 0; u < kDecLoads; ++u) t.v[u] = stream_words<S::kWords>(Vh + off[u]);
 }
 
-// partial layout: [B*Hq][n_splits][D + 2] floats: acc[0..D), m (log2 domain), l.
+// workspace layout: [counters: kDecodeCounterBytes] [partials]
+// partials: [B*Hq][n_splits][D + 2] floats: acc[0..D), m (log2 domain), l.
 template <typename E, int D, int G>
 __global__ __launch_bounds__(kDecThreads)
-void decode_partial_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
-                           const char* __restrict__ Vc, int Hkv, int64_t kv_len,
-                           int64_t head_stride_bytes, int64_t rows_per_split, int n_splits,
-                           float scale_log2e, float* __restrict__ partial) {
+void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
+                   const char* __restrict__ Vc, int Hkv, int64_t kv_len,
+                   int64_t head_stride_bytes, int64_t rows_per_split, int n_splits,
+                   float scale_log2e, uint32_t* __restrict__ counters,
+                   float* __restrict__ partial, float* __restrict__ O) {
     using S = Slice<E, D>;
     constexpr int EPL = S::kElems;
+    constexpr int W = S::kWords;
+    constexpr bool kBf16 = E::kBytes == 2;
     constexpr float kNegInf = -INFINITY;
     __shared__ float s_acc[kDecGroups][G][D];
     __shared__ float s_m[kDecGroups][G];
     __shared__ float s_l[kDecGroups][G];
+    __shared__ uint32_t s_ticket;
 
     const int split = blockIdx.x;
     const int pair = blockIdx.y;                 // b * Hkv + hkv
@@ -79,28 +138,32 @@ void decode_partial_kernel(const char* __restrict__ Q, const char* __restrict__ 
     const int hkv = pair % Hkv;
     const int Hq = Hkv * G;
     const int lane = threadIdx.x % kWaveSize;
-    const int wave = threadIdx.x / kWaveSize;
+    // the wave index is the same in all 64 lanes: keep it in a scalar register
+    // so every branch on row positions below is a scalar branch
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
     const int c = lane % kRowLanes;
     const int rg = lane / kRowLanes;
+    const int64_t hq0 = (int64_t)b * Hq + (int64_t)hkv * G;   // first query head of the group
 
-    // This lane's slice of the G query rows, pre-scaled into the log2 domain.
-    float q[G][EPL];
+    // This lane's slice of the G query rows: raw bf16 pairs for the packed dot,
+    // fp32 values otherwise.  The scale is applied to the reduced score.
+    uint32_t qw[G][W];
+    float qf[kBf16 ? 1 : G][kBf16 ? 1 : EPL];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        const int64_t hq = (int64_t)b * Hq + (int64_t)hkv * G + g;
-        Words<S::kWords> raw = load_words<S::kWords>(Q + hq * S::kRowBytes + c * S::kBytes);
-        widen<E, D>(raw, q[g]);
+        Words<W> raw = load_words<W>(Q + (hq0 + g) * S::kRowBytes + c * S::kBytes);
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) q[g][e] *= scale_log2e;
+        for (int w = 0; w < W; ++w) qw[g][w] = raw.w[w];
+        if constexpr (!kBf16) widen<E, D>(raw, qf[g]);
     }
 
     const int64_t r0 = (int64_t)split * rows_per_split;
     const int64_t r1 = (r0 + rows_per_split < kv_len) ? r0 + rows_per_split : kv_len;
-    const int64_t n_steps = (r1 - r0 + kDecRowsPerStep - 1) / kDecRowsPerStep;
     const char* Kh = Kc + (int64_t)pair * head_stride_bytes;
     const char* Vh = Vc + (int64_t)pair * head_stride_bytes;
+    const int lane_off = rg * S::kRowBytes + c * S::kBytes;
 
-    float m[G], l[G], acc[G][EPL];
+    float m[G], l[G], acc[G][EPL];    // m: running max of the RAW score (before scaling)
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         m[g] = kNegInf;
@@ -109,25 +172,35 @@ void decode_partial_kernel(const char* __restrict__ Q, const char* __restrict__ 
         for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
     }
 
-    auto consume = [&](const Tile<E, D>& t, int64_t first_row) {
+    auto consume = [&](const Tile<E, D>& t, int64_t first_row, bool ragged) {
         float s[G][kDecLoads];
 #pragma unroll
         for (int u = 0; u < kDecLoads; ++u) {
-            float kx[EPL];
-            widen<E, D>(t.k[u], kx);
+            if constexpr (kBf16) {
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                float a = q[g][0] * kx[0];
+                for (int g = 0; g < G; ++g) {
+                    float a = dot2_bf16(qw[g][0], t.k[u].w[0], 0.f);
 #pragma unroll
-                for (int e = 1; e < EPL; ++e) a = fmaf(q[g][e], kx[e], a);
-                s[g][u] = a;
+                    for (int w = 1; w < W; ++w) a = dot2_bf16(qw[g][w], t.k[u].w[w], a);
+                    s[g][u] = a;
+                }
+            } else {
+                float kx[EPL];
+                widen<E, D>(t.k[u], kx);
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    float a = qf[g][0] * kx[0];
+#pragma unroll
+                    for (int e = 1; e < EPL; ++e) a = fmaf(qf[g][e], kx[e], a);
+                    s[g][u] = a;
+                }
             }
         }
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
             for (int u = 0; u < kDecLoads; ++u) s[g][u] = row16_tree_sum(s[g][u]);
-        if (first_row + kDecRowsPerStep > r1) {          // wave-uniform: only the ragged last step
+        if (ragged) {                                    // only the last, partial tile of a range
 #pragma unroll
             for (int u = 0; u < kDecLoads; ++u) {
                 const bool valid = first_row + u * kRowsPerWaveLoad + rg < r1;
@@ -141,12 +214,13 @@ void decode_partial_kernel(const char* __restrict__ Q, const char* __restrict__ 
             float mn = m[g];
 #pragma unroll
             for (int u = 0; u < kDecLoads; ++u) mn = fmaxf(mn, s[g][u]);
-            const float ms = mn == kNegInf ? 0.f : mn;   // group has seen no valid row yet
-            const float alpha = fast_exp2(m[g] - ms);
+            // scaled max; 0 while the group has seen no valid row (avoids inf - inf)
+            const float ms = mn == kNegInf ? 0.f : mn * scale_log2e;
+            const float alpha = fast_exp2(fmaf(m[g], scale_log2e, -ms));
             float psum = 0.f;
 #pragma unroll
             for (int u = 0; u < kDecLoads; ++u) {
-                p[g][u] = fast_exp2(s[g][u] - ms);
+                p[g][u] = fast_exp2(fmaf(s[g][u], scale_log2e, -ms));
                 psum += p[g][u];
             }
             l[g] = fmaf(l[g], alpha, psum);
@@ -165,20 +239,53 @@ void decode_partial_kernel(const char* __restrict__ Q, const char* __restrict__ 
         }
     };
 
-    // Software pipeline: the loads of step j+kDecWaves are issued before the
-    // arithmetic of step j.
-    if (wave < n_steps) {
-        Tile<E, D> cur, nxt;
-        int64_t j = wave;
-        load_tile<E, D>(cur, Kh, Vh, r0 + j * kDecRowsPerStep, r1 - 1, rg, c);
-        while (true) {
-            const int64_t jn = j + kDecWaves;
-            const bool more = jn < n_steps;
-            if (more) load_tile<E, D>(nxt, Kh, Vh, r0 + jn * kDecRowsPerStep, r1 - 1, rg, c);
-            consume(cur, r0 + j * kDecRowsPerStep);
-            if (!more) break;
-            cur = nxt;
-            j = jn;
+    // This wave's tiles are j = wave, wave+4, ... of the range.  The full tiles
+    // run through a ping-pong pipeline: tile i+1 is requested before tile i is
+    // consumed, with no branch between a load and its use, so the hardware
+    // wait counters stay exact.  A ragged last tile (at most one per range) is
+    // handled afterwards with clamped loads and masked scores.
+    {
+        const int64_t n_full = (r1 - r0) / kDecRowsPerStep;                    // full tiles in the range
+        const int64_t mine = n_full > wave ? (n_full - wave + kDecWaves - 1) / kDecWaves : 0;
+        constexpr int64_t kStride = (int64_t)kDecWaves * kDecRowsPerStep;
+        int64_t row = r0 + (int64_t)wave * kDecRowsPerStep;
+        if (mine > 0) {
+            Tile<E, D> ta, tb;
+            // The scheduling barriers pin each batch of loads ahead of the
+            // arithmetic on the other tile; without them the compiler sinks
+            // the loads next to their first use and the prefetch is lost.
+            load_tile<E, D>(ta, Kh, Vh, row, lane_off);
+            __builtin_amdgcn_sched_barrier(0);
+            int64_t left = mine;                       // tiles not yet consumed; ta holds the first
+            while (left > 2) {
+                load_tile<E, D>(tb, Kh, Vh, row + kStride, lane_off);
+                __builtin_amdgcn_sched_barrier(0);
+                consume(ta, row, false);
+                __builtin_amdgcn_sched_barrier(0);
+                load_tile<E, D>(ta, Kh, Vh, row + 2 * kStride, lane_off);
+                __builtin_amdgcn_sched_barrier(0);
+                consume(tb, row + kStride, false);
+                __builtin_amdgcn_sched_barrier(0);
+                row += 2 * kStride;
+                left -= 2;
+            }
+            if (left == 2) {
+                load_tile<E, D>(tb, Kh, Vh, row + kStride, lane_off);
+                __builtin_amdgcn_sched_barrier(0);
+                consume(ta, row, false);
+                consume(tb, row + kStride, false);
+                row += 2 * kStride;
+            } else {
+                consume(ta, row, false);
+                row += kStride;
+            }
+        }
+        const int64_t tail_rows = (r1 - r0) % kDecRowsPerStep;
+        if (tail_rows != 0 && (n_full % kDecWaves) == wave) {
+            Tile<E, D> tt;
+            const int64_t first = r0 + n_full * kDecRowsPerStep;
+            load_tile_clamped<E, D>(tt, Kh, Vh, first, r1 - 1, rg, c);
+            consume(tt, first, true);
         }
     }
 
@@ -189,7 +296,7 @@ void decode_partial_kernel(const char* __restrict__ Q, const char* __restrict__ 
 #pragma unroll
         for (int e = 0; e < EPL; ++e) s_acc[grp][g][c * EPL + e] = acc[g][e];
         if (c == 0) {
-            s_m[grp][g] = m[g];
+            s_m[grp][g] = m[g] * scale_log2e;     // -inf stays -inf (scale > 0)
             s_l[grp][g] = l[g];
         }
     }
@@ -208,31 +315,73 @@ void decode_partial_kernel(const char* __restrict__ Q, const char* __restrict__ 
             num = fmaf(w, s_acc[i][g][d], num);
             den = fmaf(w, s_l[i][g], den);
         }
-        const int64_t hq = (int64_t)b * Hq + (int64_t)hkv * G + g;
-        float* out = partial + (hq * n_splits + split) * (D + 2);
-        out[d] = num;
+        // Device-scope stores: written through to the level every compute unit
+        // of the device reads from, so the merging workgroup below sees them
+        // without any bulk cache write-back.
+        float* out = partial + ((hq0 + g) * n_splits + split) * (D + 2);
+        publish(out + d, num);
         if (d == 0) {
-            out[D] = mx;
-            out[D + 1] = den;
+            publish(out + D, mx);
+            publish(out + D + 1, den);
         }
     }
-}
 
-template <int D>
-__global__ __launch_bounds__(D)
-void decode_merge_kernel(const float* __restrict__ partial, int n_splits, float* __restrict__ O) {
-    const int64_t hq = blockIdx.x;               // b * Hq + hq
-    const int d = threadIdx.x;
-    const float* p = partial + hq * n_splits * (D + 2);
-    float mx = -INFINITY;
-    for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, p[s * (D + 2) + D]);
-    float num = 0.f, den = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
-        const float w = fast_exp2(p[s * (D + 2) + D] - mx);   // every launched range has >= 1 row
-        num = fmaf(w, p[s * (D + 2) + d], num);
-        den = fmaf(w, p[s * (D + 2) + D + 1], den);
+    // ---- the last workgroup of this KV head merges all row ranges ---------
+    // Hand-over protocol: every partial is written with a device-scope store;
+    // the barrier waits until this workgroup's stores have completed; one lane
+    // then takes a ticket with a device-scope atomic.  The workgroup that draws
+    // the last ticket re-reads all partials with device-scope loads.  No lane
+    // ever waits on another workgroup, so nothing here can hang.
+    __syncthreads();
+    if (threadIdx.x == 0)
+        s_ticket = __hip_atomic_fetch_add(&counters[pair], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (s_ticket != (uint32_t)(n_splits - 1)) return;
+    // Phase 1: (m, l) of every (head, range) into LDS -- one memory round trip.
+    // The accumulator staging area is free again after the barriers above.
+    float* s_pm = &s_acc[0][0][0];                 // [G][n_splits] maxima
+    float* s_pl = s_pm + G * kDecodeMaxSplits;     // [G][n_splits] denominators
+    static_assert(2 * G * kDecodeMaxSplits <= kDecGroups * G * D, "merge staging does not fit");
+    for (int i = threadIdx.x; i < G * n_splits; i += kDecThreads) {
+        const int g = i / n_splits;
+        const int sp = i % n_splits;
+        const float* p = partial + ((hq0 + g) * n_splits + sp) * (D + 2);
+        s_pm[g * kDecodeMaxSplits + sp] = fetch(p + D);
+        s_pl[g * kDecodeMaxSplits + sp] = fetch(p + D + 1);
     }
-    O[hq * D + d] = num / den;
+    __syncthreads();
+    // Phase 2: each lane owns output elements (g, d); the partial accumulators
+    // are fetched kMergeBatch at a time so the loads overlap.
+    constexpr int kMergeBatch = 16;
+    for (int o = threadIdx.x; o < G * D; o += kDecThreads) {
+        const int g = o / D;
+        const int d = o % D;
+        const float* p = partial + (hq0 + g) * n_splits * (D + 2) + d;
+        const float* pm = s_pm + g * kDecodeMaxSplits;
+        const float* pl = s_pl + g * kDecodeMaxSplits;
+        float mx = kNegInf;
+        for (int sp = 0; sp < n_splits; ++sp) mx = fmaxf(mx, pm[sp]);
+        float num = 0.f, den = 0.f;
+        for (int s0 = 0; s0 < n_splits; s0 += kMergeBatch) {
+            float v[kMergeBatch];
+#pragma unroll
+            for (int i = 0; i < kMergeBatch; ++i) {
+                const int sp = s0 + i < n_splits ? s0 + i : n_splits - 1;   // clamp: in bounds, weight 0 below
+                v[i] = fetch(p + sp * (D + 2));
+            }
+#pragma unroll
+            for (int i = 0; i < kMergeBatch; ++i) {
+                if (s0 + i < n_splits) {
+                    const float w = fast_exp2(pm[s0 + i] - mx);            // every range has >= 1 row
+                    num = fmaf(w, v[i], num);
+                    den = fmaf(w, pl[s0 + i], den);
+                }
+            }
+        }
+        O[(hq0 + g) * D + d] = num / den;
+    }
+    // leave the counter ready for the next call on this workspace
+    if (threadIdx.x == 0) __hip_atomic_store(&counters[pair], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 int32_t decode_max_splits(int64_t kv_len) {
@@ -264,25 +413,25 @@ DecodePlan decode_plan(int32_t B, int32_t Hkv, int64_t kv_len, int32_t requested
 template <typename E, int D, int G>
 static l2kv_status launch_decode(const void* Q, const void* Kc, const void* Vc, int32_t B, int32_t Hq,
                                  int32_t Hkv, int64_t kv_len, int64_t kv_head_stride, float scale,
-                                 const DecodePlan& plan, float* O, float* workspace,
+                                 const DecodePlan& plan, float* O, void* workspace,
                                  hipStream_t stream) {
+    (void)Hq;
     const float scale_log2e = scale * 1.4426950408889634f;
+    uint32_t* counters = static_cast<uint32_t*>(workspace);
+    float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + decode_counter_bytes(B, Hkv));
     dim3 grid((unsigned)plan.n_splits, (unsigned)(B * Hkv));
-    hipLaunchKernelGGL((decode_partial_kernel<E, D, G>), grid, dim3(kDecThreads), 0, stream,
+    hipLaunchKernelGGL((decode_kernel<E, D, G>), grid, dim3(kDecThreads), 0, stream,
                        static_cast<const char*>(Q), static_cast<const char*>(Kc),
                        static_cast<const char*>(Vc), (int)Hkv, kv_len,
                        kv_head_stride * (int64_t)E::kBytes, plan.rows_per_split, (int)plan.n_splits,
-                       scale_log2e, workspace);
-    if (hipGetLastError() != hipSuccess) return L2KV_ERR_LAUNCH;
-    hipLaunchKernelGGL((decode_merge_kernel<D>), dim3((unsigned)(B * Hq)), dim3(D), 0, stream,
-                       workspace, (int)plan.n_splits, O);
+                       scale_log2e, counters, partial, O);
     return launch_status();
 }
 
 template <typename E, int D>
 static l2kv_status decode_by_group(int G, const void* Q, const void* Kc, const void* Vc, int32_t B,
                                    int32_t Hq, int32_t Hkv, int64_t kv_len, int64_t kv_head_stride,
-                                   float scale, const DecodePlan& plan, float* O, float* workspace,
+                                   float scale, const DecodePlan& plan, float* O, void* workspace,
                                    hipStream_t stream) {
 #define L2KV_G(N)                                                                                   \
     case N:                                                                                         \
@@ -298,7 +447,7 @@ static l2kv_status decode_by_group(int G, const void* Q, const void* Kc, const v
 l2kv_status decode_dispatch(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt, int32_t B,
                             int32_t Hq, int32_t Hkv, int64_t kv_len, int32_t D,
                             int64_t kv_head_stride, float scale, const DecodePlan& plan, float* O,
-                            float* workspace, hipStream_t stream) {
+                            void* workspace, hipStream_t stream) {
     const int G = Hq / Hkv;
     if (dt == L2KV_F32) {
         return D == 64 ? decode_by_group<F32, 64>(G, Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride,

@@ -24,8 +24,10 @@ constexpr int kDppMirror = 0x140;     // lane i <- lane 15-i within 16 lanes
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_read(float v) {
+    // Full row/bank masks with bound_ctrl: every lane reads a live lane, and the
+    // compiler may fold the swizzle into the consuming VALU instruction.
     int iv = __builtin_bit_cast(int, v);
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(iv, iv, CTRL, 0xf, 0xf, false));
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, iv, CTRL, 0xf, 0xf, true));
 }
 
 // Sum over the 16 lanes of a row group as a balanced binary tree over

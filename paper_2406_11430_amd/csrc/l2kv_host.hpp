@@ -35,11 +35,17 @@ struct DecodePlan {
 constexpr int kDecodeMaxSplits = 256;
 constexpr int kDecodeRowTile = 64;   // rows one workgroup consumes per step (4 waves x 16)
 int32_t decode_max_splits(int64_t kv_len);
+// The decode workspace starts with one arrival counter per (sequence, KV head),
+// padded to 256 bytes; the split partials follow.
+inline size_t decode_counter_bytes(int32_t B, int32_t Hkv) {
+    const size_t raw = static_cast<size_t>(B) * static_cast<size_t>(Hkv) * sizeof(uint32_t);
+    return (raw + 255) / 256 * 256;
+}
 DecodePlan decode_plan(int32_t B, int32_t Hkv, int64_t kv_len, int32_t requested_splits);
 
 l2kv_status decode_dispatch(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt, int32_t B,
                             int32_t Hq, int32_t Hkv, int64_t kv_len, int32_t D,
                             int64_t kv_head_stride, float scale, const DecodePlan& plan, float* O,
-                            float* workspace, hipStream_t stream);
+                            void* workspace, hipStream_t stream);
 
 }  // namespace l2kv

@@ -125,7 +125,7 @@ def test_compact_validation(lib):
 def test_decode_validation(lib):
     f = lib.l2kv_decode_attn
     ws = lib.l2kv_decode_workspace_bytes(2, 8, 100, 128)
-    assert ws == 2 * 8 * lib.l2kv_decode_max_splits(100) * 130 * 4
+    assert ws == 256 + 2 * 8 * lib.l2kv_decode_max_splits(100) * 130 * 4   # counters + partials
     a = (P, P, P, 1, 2, 8, 2, 100, 128, 12800, 0.0, P, P, ws, None)
 
     def call(**kw):

@@ -61,7 +61,7 @@ def gpu_decode(Qd, Kd, Vd, n_splits=None, scale=0.0):
     B, Hq, D = Qd.shape
     n = Kd.shape[2]
     O = torch.full((B, Hq, D), float("nan"), dtype=torch.float32, device=Qd.device)
-    ws = torch.empty(l2kv.l2kv_decode_workspace_bytes(B, Hq, n, D), dtype=torch.uint8, device=Qd.device)
+    ws = torch.zeros(l2kv.l2kv_decode_workspace_bytes(B, Hq, n, D), dtype=torch.uint8, device=Qd.device)
     l2kv.l2kv_decode_attn_splits(Qd, Kd, Vd, O, ws, scale=scale, n_splits=n_splits)
     return O
 
@@ -225,7 +225,7 @@ def test_decode_ragged_lengths_and_split_counts(dev, n):
         assert err <= ATTN_BAR, (n, s, err)
         outs.append(got)
     for o in outs[1:]:                       # independent of the split count up to fp32 rounding
-        assert np.abs(o - outs[0]).max() <= 2e-5
+        assert np.abs(o - outs[0]).max() <= 5e-5 * max(1.0, np.abs(want).max())
 
 
 def test_decode_closed_forms_on_gpu(dev):

@@ -34,6 +34,12 @@ from paper_2406_11430_amd import synth         # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 
+# HBM bytes of ONE decode-attention launch at the C3 per-layer shape, from two
+# rocprofv3 --pmc runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a
+# plain 1 GiB copy in the same runs): profiles/hot_path_hbm_traffic_pmc.md.
+# Offline measurement; reported only when the timed shape is that shape.
+MEASURED_DECODE_TRAFFIC_BYTES = {("bf16", 4, 8, 32, 128, 16384): (263195 + 697) * 1024}
+
 
 # ----------------------------------------------------------------- byte model
 def compress_bytes_per_layer(cfg, k):
@@ -82,6 +88,11 @@ class Workload:
                                   dtype=torch.uint8, device=dev)
         self.dec_ws = torch.zeros(l2kv.l2kv_decode_workspace_bytes(B, Hq, self.k, D),
                                   dtype=torch.uint8, device=dev)
+        # per-layer views made once, so the timed loop only marshals pointers
+        self.Q_v = [[self.Q[s, l] for l in range(L)] for s in range(cfg.decode_steps)]
+        self.Kc_v = [self.Kc[l] for l in range(L)]
+        self.Vc_v = [self.Vc[l] for l in range(L)]
+        self.O_v = [self.O[l] for l in range(L)]
         torch.cuda.synchronize()
 
     # -- the hot path: every call below is one C-ABI entry point ---------------
@@ -91,9 +102,9 @@ class Workload:
         l2kv.l2kv_compact(self.K, self.V, self.idx, self.Kc, self.Vc)
 
     def decode_step(self, step):
+        Qs, ws = self.Q_v[step], self.dec_ws
         for layer in range(self.cfg.L):
-            l2kv.l2kv_decode_attn(self.Q[step, layer], self.Kc[layer], self.Vc[layer],
-                                  self.O[layer], self.dec_ws)
+            l2kv.l2kv_decode_attn(Qs[layer], self.Kc_v[layer], self.Vc_v[layer], self.O_v[layer], ws)
 
     def decode_all(self):
         for step in range(self.cfg.decode_steps):
@@ -154,9 +165,12 @@ def main():
     ap.add_argument("--workload", default="C3", choices=sorted(synth.CONFIGS))
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
     ap.add_argument("--decode-steps", type=int, default=0, help="override decode steps (debug)")
-    ap.add_argument("--cpu-layers", type=int, default=4)
-    ap.add_argument("--cpu-decode-steps", type=int, default=4)
+    ap.add_argument("--cpu-layers", type=int, default=8)
+    ap.add_argument("--cpu-decode-steps", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device copy (torch) before the timed region: "
+                         "the known-size kernel that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -183,6 +197,13 @@ def main():
     dec_bytes_layer = decode_bytes_per_layer(cfg, k)
     dec_bytes = dec_bytes_layer * cfg.L * cfg.decode_steps
     step_bytes = comp_bytes + dec_bytes
+
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         w.step()
@@ -243,7 +264,9 @@ def main():
         "roofline": {
             "kernel": "decode attention (one l2kv_decode_attn call on one layer)",
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": MEASURED_DECODE_TRAFFIC_BYTES.get((cfg.dtype, cfg.B, cfg.Hkv, cfg.Hq, cfg.D, k)),
+            "traffic_unit": "bytes per launch (rocprofv3 --pmc, see profiles/)",
             "bytes_per_launch": dec_bytes_layer, "us_per_launch": round(us_per_layer_call, 3),
             "timing": "HIP events on the launch stream around all %d calls of each step" % n_decode_launch,
         },

@@ -4,15 +4,16 @@
 // HBM, so the kernel is a read stream of Kc and Vc with the arithmetic folded
 // in, and the scores never touch memory.
 //
-// Decomposition: grid (row range, sequence x KV head).  A workgroup of 4 waves
-// streams its row range once for all G = Hq/Hkv query heads of the KV head.
-// 16 lanes share a row (16 bytes each), a wave covers 16 rows of K and of V
-// per step (4 + 4 non-temporal loads per lane) and always has the next step's
-// rows in flight while it computes on the current ones (two register tiles,
-// ping-pong, no branch around the prefetch so the wait counters stay exact).
-// Every 16-lane row group runs its own online softmax (running max m,
-// denominator l, weighted value sum acc), so the only cross-lane traffic in
-// the loop is the 4-step DPP tree of each dot product.
+// Decomposition: grid (split, sequence x KV head).  The n_splits workgroups of a
+// KV head take turns on consecutive 64-row blocks of its cache and stream them
+// once for all G = Hq/Hkv query heads.  16 lanes share a row (16 bytes each),
+// a wave covers 16 rows of K and of V per step (4 + 4 non-temporal loads per
+// lane) and always has its next tile in flight while it computes on the
+// current one (two register tiles, ping-pong, no branch between a load and its
+// use so the wait counters stay exact).  Every 16-lane row group runs its own
+// online softmax (running max m, denominator l, weighted value sum acc), so the
+// only cross-lane traffic in the loop is the 4-step DPP tree of each dot
+// product.
 //
 // bf16 caches: q.k uses the packed bf16 dot instruction with fp32 accumulate
 // (both operands are exact bf16 inputs); the softmax scale is applied to the
@@ -21,7 +22,7 @@
 // At the end the 16 row groups of the workgroup are merged through LDS and one
 // partial (acc[D], m, l) per query head goes to the workspace.  The workgroup
 // that finishes last for its KV head (device-scope counter in the workspace)
-// merges the partials of all row ranges and writes O: one kernel per call.
+// merges the partials of all workgroups and writes O: one kernel per call.
 //
 // Scores are kept in the log2 domain so the exponentials are bare v_exp_f32.
 #include "l2kv_device.hpp"
@@ -119,7 +120,7 @@ template <typename E, int D, int G>
 __global__ __launch_bounds__(kDecThreads)
 void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
                    const char* __restrict__ Vc, int Hkv, int64_t kv_len,
-                   int64_t head_stride_bytes, int64_t rows_per_split, int n_splits,
+                   int64_t head_stride_bytes, int n_splits,
                    float scale_log2e, uint32_t* __restrict__ counters,
                    float* __restrict__ partial, float* __restrict__ O) {
     using S = Slice<E, D>;
@@ -157,8 +158,7 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
         if constexpr (!kBf16) widen<E, D>(raw, qf[g]);
     }
 
-    const int64_t r0 = (int64_t)split * rows_per_split;
-    const int64_t r1 = (r0 + rows_per_split < kv_len) ? r0 + rows_per_split : kv_len;
+    const int64_t r1 = kv_len;                   // rows at or past r1 do not exist
     const char* Kh = Kc + (int64_t)pair * head_stride_bytes;
     const char* Vh = Vc + (int64_t)pair * head_stride_bytes;
     const int lane_off = rg * S::kRowBytes + c * S::kBytes;
@@ -239,16 +239,25 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
         }
     };
 
-    // This wave's tiles are j = wave, wave+4, ... of the range.  The full tiles
-    // run through a ping-pong pipeline: tile i+1 is requested before tile i is
-    // consumed, with no branch between a load and its use, so the hardware
-    // wait counters stay exact.  A ragged last tile (at most one per range) is
-    // handled afterwards with clamped loads and masked scores.
+    // Work assignment.  The head's rows are cut into 16-row tiles; tile t goes to
+    // workgroup (t / 4) % n_splits, wave t % 4: the workgroups of a KV head take
+    // turns on consecutive 64-row blocks.  Every workgroup therefore sweeps the
+    // whole address range of the head, which evens out the differences in
+    // memory distance between compute dies and address ranges that a
+    // contiguous range per workgroup would expose.
+    //
+    // The full tiles run through a ping-pong pipeline: tile i+1 is requested
+    // before tile i is consumed, with no branch between a load and its use, so
+    // the hardware wait counters stay exact.  The ragged last tile of the head
+    // (if any) is handled by its owner afterwards with clamped loads and
+    // masked scores.
     {
-        const int64_t n_full = (r1 - r0) / kDecRowsPerStep;                    // full tiles in the range
-        const int64_t mine = n_full > wave ? (n_full - wave + kDecWaves - 1) / kDecWaves : 0;
-        constexpr int64_t kStride = (int64_t)kDecWaves * kDecRowsPerStep;
-        int64_t row = r0 + (int64_t)wave * kDecRowsPerStep;
+        const int64_t n_full = kv_len / kDecRowsPerStep;                       // full tiles in the head
+        const int64_t first_tile = (int64_t)split * kDecWaves + wave;
+        const int64_t tile_stride = (int64_t)n_splits * kDecWaves;
+        const int64_t mine = n_full > first_tile ? (n_full - first_tile + tile_stride - 1) / tile_stride : 0;
+        const int64_t kStride = tile_stride * kDecRowsPerStep;                 // rows between my tiles
+        int64_t row = first_tile * kDecRowsPerStep;
         if (mine > 0) {
             Tile<E, D> ta, tb;
             // The scheduling barriers pin each batch of loads ahead of the
@@ -274,16 +283,14 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
                 __builtin_amdgcn_sched_barrier(0);
                 consume(ta, row, false);
                 consume(tb, row + kStride, false);
-                row += 2 * kStride;
             } else {
                 consume(ta, row, false);
-                row += kStride;
             }
         }
-        const int64_t tail_rows = (r1 - r0) % kDecRowsPerStep;
-        if (tail_rows != 0 && (n_full % kDecWaves) == wave) {
+        if (kv_len % kDecRowsPerStep != 0 && (n_full / kDecWaves) % n_splits == split &&
+            n_full % kDecWaves == wave) {
             Tile<E, D> tt;
-            const int64_t first = r0 + n_full * kDecRowsPerStep;
+            const int64_t first = n_full * kDecRowsPerStep;
             load_tile_clamped<E, D>(tt, Kh, Vh, first, r1 - 1, rg, c);
             consume(tt, first, true);
         }
@@ -394,19 +401,16 @@ DecodePlan decode_plan(int32_t B, int32_t Hkv, int64_t kv_len, int32_t requested
     const int64_t pairs = (int64_t)B * Hkv;
     int64_t want = requested_splits;
     if (want <= 0) {
-        // Two resident workgroups per compute unit, all started in one wave of
-        // the grid so every range finishes at about the same time.
-        const int64_t target = 2LL * device_compute_units();
+        // One workgroup (4 waves) per compute unit, all resident at once: measured
+        // best for this stream; more workgroups only lengthen the final merge.
+        const int64_t target = device_compute_units();
         want = (target + pairs - 1) / pairs;
     }
     const int64_t cap = decode_max_splits(kv_len);
     if (want > cap) want = cap;
     if (want < 1) want = 1;
-    int64_t rps = (kv_len + want - 1) / want;
-    rps = (rps + kDecodeRowTile - 1) / kDecodeRowTile * kDecodeRowTile;
     DecodePlan plan;
-    plan.rows_per_split = rps;
-    plan.n_splits = (int32_t)((kv_len + rps - 1) / rps);
+    plan.n_splits = (int32_t)want;
     return plan;
 }
 
@@ -423,7 +427,7 @@ static l2kv_status launch_decode(const void* Q, const void* Kc, const void* Vc, 
     hipLaunchKernelGGL((decode_kernel<E, D, G>), grid, dim3(kDecThreads), 0, stream,
                        static_cast<const char*>(Q), static_cast<const char*>(Kc),
                        static_cast<const char*>(Vc), (int)Hkv, kv_len,
-                       kv_head_stride * (int64_t)E::kBytes, plan.rows_per_split, (int)plan.n_splits,
+                       kv_head_stride * (int64_t)E::kBytes, (int)plan.n_splits,
                        scale_log2e, counters, partial, O);
     return launch_status();
 }

@@ -27,10 +27,10 @@ l2kv_status compact_dispatch(const void* K, const void* V, l2kv_dtype dt, const 
                              int64_t n_heads, int64_t T, int64_t k, int32_t D, int64_t head_stride,
                              void* Kc, void* Vc, hipStream_t stream);
 
-// Row-range decomposition of decode attention over kv_len rows.
+// Decomposition of decode attention over the kv_len rows of a KV head:
+// n_splits workgroups take turns on consecutive 64-row blocks.
 struct DecodePlan {
-    int32_t n_splits;        // row ranges per KV head actually launched
-    int64_t rows_per_split;  // multiple of the block's row tile
+    int32_t n_splits;        // workgroups per KV head (each owns >= 1 row)
 };
 constexpr int kDecodeMaxSplits = 256;
 constexpr int kDecodeRowTile = 64;   // rows one workgroup consumes per step (4 waves x 16)

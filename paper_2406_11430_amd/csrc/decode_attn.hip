@@ -344,48 +344,62 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
         s_ticket = __hip_atomic_fetch_add(&counters[pair], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (s_ticket != (uint32_t)(n_splits - 1)) return;
-    // Phase 1: (m, l) of every (head, range) into LDS -- one memory round trip.
-    // The accumulator staging area is free again after the barriers above.
-    float* s_pm = &s_acc[0][0][0];                 // [G][n_splits] maxima
-    float* s_pl = s_pm + G * kDecodeMaxSplits;     // [G][n_splits] denominators
-    static_assert(2 * G * kDecodeMaxSplits <= kDecGroups * G * D, "merge staging does not fit");
-    for (int i = threadIdx.x; i < G * n_splits; i += kDecThreads) {
-        const int g = i / n_splits;
-        const int sp = i % n_splits;
-        const float* p = partial + ((hq0 + g) * n_splits + sp) * (D + 2);
-        s_pm[g * kDecodeMaxSplits + sp] = fetch(p + D);
-        s_pl[g * kDecodeMaxSplits + sp] = fetch(p + D + 1);
+    // Each lane owns up to kOut output elements (g, d) and fetches, for a batch
+    // of workgroups at a time, their accumulator element together with their
+    // (m, l): all loads of a batch are independent, so the whole merge costs
+    // about one memory round trip per batch (one batch up to 8 workgroups).
+    constexpr int kOut = (G * D + kDecThreads - 1) / kDecThreads;
+    constexpr int kMergeBatch = 8;
+    float num[kOut], den[kOut], mx[kOut];
+#pragma unroll
+    for (int j = 0; j < kOut; ++j) {
+        num[j] = 0.f;
+        den[j] = 0.f;
+        mx[j] = kNegInf;
     }
-    __syncthreads();
-    // Phase 2: each lane owns output elements (g, d); the partial accumulators
-    // are fetched kMergeBatch at a time so the loads overlap.
-    constexpr int kMergeBatch = 16;
-    for (int o = threadIdx.x; o < G * D; o += kDecThreads) {
-        const int g = o / D;
-        const int d = o % D;
-        const float* p = partial + (hq0 + g) * n_splits * (D + 2) + d;
-        const float* pm = s_pm + g * kDecodeMaxSplits;
-        const float* pl = s_pl + g * kDecodeMaxSplits;
-        float mx = kNegInf;
-        for (int sp = 0; sp < n_splits; ++sp) mx = fmaxf(mx, pm[sp]);
-        float num = 0.f, den = 0.f;
-        for (int s0 = 0; s0 < n_splits; s0 += kMergeBatch) {
-            float v[kMergeBatch];
+    for (int s0 = 0; s0 < n_splits; s0 += kMergeBatch) {
+        float v[kOut][kMergeBatch], pm[kOut][kMergeBatch], pl[kOut][kMergeBatch];
+#pragma unroll
+        for (int j = 0; j < kOut; ++j) {
+            const int o = threadIdx.x + j * kDecThreads;
+            const int oo = o < G * D ? o : 0;                               // idle lanes re-read element 0
+            const int g = oo / D;
+            const int d = oo % D;
 #pragma unroll
             for (int i = 0; i < kMergeBatch; ++i) {
-                const int sp = s0 + i < n_splits ? s0 + i : n_splits - 1;   // clamp: in bounds, weight 0 below
-                v[i] = fetch(p + sp * (D + 2));
+                const int sp = s0 + i < n_splits ? s0 + i : n_splits - 1;   // clamp: in bounds, ignored below
+                const float* p = partial + ((hq0 + g) * n_splits + sp) * (D + 2);
+                v[j][i] = fetch(p + d);
+                pm[j][i] = fetch(p + D);
+                pl[j][i] = fetch(p + D + 1);
             }
+        }
+#pragma unroll
+        for (int j = 0; j < kOut; ++j) {
+            float bm = mx[j];
+#pragma unroll
+            for (int i = 0; i < kMergeBatch; ++i)
+                if (s0 + i < n_splits) bm = fmaxf(bm, pm[j][i]);
+            const float keep = mx[j] == kNegInf ? 0.f : fast_exp2(mx[j] - bm);
+            num[j] *= keep;
+            den[j] *= keep;
 #pragma unroll
             for (int i = 0; i < kMergeBatch; ++i) {
                 if (s0 + i < n_splits) {
-                    const float w = fast_exp2(pm[s0 + i] - mx);            // every range has >= 1 row
-                    num = fmaf(w, v[i], num);
-                    den = fmaf(w, pl[s0 + i], den);
+                    // -inf: that workgroup saw no row (cannot happen with the current
+                    // assignment, where every workgroup owns at least one row)
+                    const float w = pm[j][i] == kNegInf ? 0.f : fast_exp2(pm[j][i] - bm);
+                    num[j] = fmaf(w, v[j][i], num[j]);
+                    den[j] = fmaf(w, pl[j][i], den[j]);
                 }
             }
+            mx[j] = bm;
         }
-        O[(hq0 + g) * D + d] = num / den;
+    }
+#pragma unroll
+    for (int j = 0; j < kOut; ++j) {
+        const int o = threadIdx.x + j * kDecThreads;
+        if (o < G * D) O[hq0 * D + o] = num[j] / den[j];
     }
     // leave the counter ready for the next call on this workspace
     if (threadIdx.x == 0) __hip_atomic_store(&counters[pair], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -4,12 +4,18 @@
 // the lowest-norm keys; Eq. 5: exactly m pairs dropped per layer and head)
 // with ties resolved towards the lower token index.
 //
-// One workgroup of 1024 lanes per head.  The keys (norm bits, complemented for
+// One workgroup of 1024 lanes per head (512 for the packed variant below).  The keys (norm bits, complemented for
 // the keep-highest control) sit in registers -- 32 per lane covers 32k tokens
 // -- so nothing is re-read from memory.  The k-th smallest key tau is found
 // exactly by a 32-step binary search on its bits: step b counts the keys below
 // (prefix | 1<<b) with wave ballots + popcounts (scalar unit), one LDS atomic
 // per wave and one barrier.  No histogram, no data-dependent contention.
+// Heads of up to 131072 tokens use the same search on packed halves: the upper
+// 16 bits of all keys fit the registers two to a word (16 steps), then the
+// lower 16 bits of the keys that tie on the upper half are packed the same way
+// (16 more steps); the keys are read three more times from L2 (repack, count,
+// emit) instead of 32.  Longer heads fall back to re-reading the keys in every
+// step.
 // The emit is ordered: every wave owns a contiguous token range, so a prefix
 // over the 16 wave totals plus a running ballot prefix gives each kept token
 // its output slot; keys equal to tau are admitted in token order until the
@@ -27,13 +33,21 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
-// E > 0: keys of the head fit E per lane and are cached in registers.
+// The packed variant runs 512 lanes with twice the register budget per lane:
+// 128 words of two 16-bit halves = 256 keys per lane, 131072 per workgroup.
+constexpr int kSelPackedThreads = 512;
+constexpr int kSelPackedRegs = 128;
+
+// E > 0 : keys of the head fit E per lane and are cached in registers.
 // E == 0: streaming variant, keys are re-read from memory (L2) in every pass.
+// E == -1: packed variant, 256 keys per lane as 16-bit halves (T <= 131072).
 template <int E>
-__global__ __launch_bounds__(kSelThreads)
+__global__ __launch_bounds__(E == -1 ? kSelPackedThreads : kSelThreads)
 void select_kernel(const uint32_t* __restrict__ norm_bits, int64_t T, uint32_t k, uint32_t flip,
                    int32_t* __restrict__ kept_idx, int32_t* __restrict__ kept_count) {
     constexpr bool kInRegs = E > 0;
+    constexpr bool kPacked = E == -1;
+    constexpr int kWaves = (kPacked ? kSelPackedThreads : kSelThreads) / kWaveSize;
     __shared__ uint32_t s_count[32];
     __shared__ uint32_t s_lt[kSelWaves];
     __shared__ uint32_t s_eq[kSelWaves];
@@ -45,14 +59,31 @@ void select_kernel(const uint32_t* __restrict__ norm_bits, int64_t T, uint32_t k
 
     // Wave w owns tokens [w*span, (w+1)*span), span a multiple of 64; iteration
     // e of lane l looks at token w*span + e*64 + l.
-    const int64_t iters = kInRegs ? E : (((T + kSelWaves - 1) / kSelWaves + kWaveSize - 1) / kWaveSize);
+    const int64_t iters = kInRegs ? E
+                          : kPacked ? 2 * kSelPackedRegs
+                                    : (((T + kWaves - 1) / kWaves + kWaveSize - 1) / kWaveSize);
     const int64_t span = iters * kWaveSize;
-    const int64_t t0 = wave * span + lane;
+    // Token positions fit 32 bits: T < 2^31 and the padded range ends below T + 2^17.
+    const uint32_t t0 = (uint32_t)(wave * span + lane);
+    const uint32_t T32 = (uint32_t)T;
 
-    auto fetch = [&](int64_t e) -> uint32_t {
-        const int64_t t = t0 + e * kWaveSize;
-        return t < T ? (src[t] ^ flip) : 0xffffffffu;   // padding can never be "below"
+    // Branch-free: positions past the end re-read the last key (in bounds) and
+    // are replaced by the largest key, which is never "below" anything.  Such
+    // padding sits after every real token, so in the ordered emit it is reached
+    // only after all real keys equal to tau, when the budget is already met.
+    // `base` is this lane's first position, passed through launder() by every
+    // pass that re-reads the keys: otherwise the compiler keeps all addresses
+    // and bounds predicates of one pass alive for the next and spills them.
+    auto launder = [](uint32_t x) -> uint32_t {
+        asm volatile("" : "+v"(x));
+        return x;
     };
+    auto fetch_at = [&](uint32_t base, int64_t e) -> uint32_t {
+        const uint32_t t = base + (uint32_t)e * kWaveSize;
+        const uint32_t v = src[t < T32 ? t : T32 - 1] ^ flip;
+        return t < T32 ? v : 0xffffffffu;
+    };
+    auto fetch = [&](int64_t e) -> uint32_t { return fetch_at(t0, e); };
 
     uint32_t regs[kInRegs ? E : 1];
     if constexpr (kInRegs) {
@@ -65,21 +96,83 @@ void select_kernel(const uint32_t* __restrict__ norm_bits, int64_t T, uint32_t k
     // ---- k-th smallest key by binary search on its bits (MSB first) -------
     uint32_t prefix = 0;     // tau so far
     uint32_t less = 0;       // number of keys < prefix
-    for (int bit = 31; bit >= 0; --bit) {
-        const uint32_t cand = prefix | (1u << bit);
-        uint32_t cnt = 0;
-        if constexpr (kInRegs) {
+    if constexpr (kPacked) {
+        uint32_t pk[kSelPackedRegs];
+        // one 16-step search over the packed halves in pk; `want` keys are sought
+        auto search16 = [&](int count_slot, uint32_t want, uint32_t& found, uint32_t& below_found) {
+            uint32_t pre = 0, lo = 0;
+            for (int bit = 15; bit >= 0; --bit) {
+                const uint32_t cand = pre | (1u << bit);
+                // per-lane counters here (compare + add-with-carry): 128 wave ballots
+                // per step would need more scalar registers than there are
+                uint32_t mine = 0;
 #pragma unroll
-            for (int e = 0; e < E; ++e) cnt += __popcll(__ballot(regs[e] < cand));
-        } else {
-            for (int64_t e = 0; e < iters; ++e) cnt += __popcll(__ballot(fetch(e) < cand));
+                for (int r = 0; r < kSelPackedRegs; ++r) {
+                    mine += (pk[r] & 0xffffu) < cand ? 1u : 0u;
+                    mine += (pk[r] >> 16) < cand ? 1u : 0u;
+                }
+                uint32_t cnt = mine;
+#pragma unroll
+                for (int off = kWaveSize / 2; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off);
+                if (lane == 0 && cnt) atomicAdd(&s_count[count_slot + bit], cnt);
+                __syncthreads();
+                const uint32_t below = s_count[count_slot + bit];
+                if (below < want) {
+                    pre = cand;
+                    lo = below;
+                }
+            }
+            found = pre;
+            below_found = lo;
+        };
+        // upper halves of all keys (padding reads as 0xffff and is never "below")
+        // (batches of 4 words, fenced for the scheduler: issuing all 128 loads and
+        // their bounds predicates at once would not fit the register files)
+        const uint32_t base1 = launder(t0);
+#pragma unroll
+        for (int r0 = 0; r0 < kSelPackedRegs; r0 += 4) {
+#pragma unroll
+            for (int r = r0; r < r0 + 4; ++r)
+                pk[r] = (fetch_at(base1, 2 * r) >> 16) | (fetch_at(base1, 2 * r + 1) & 0xffff0000u);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (lane == 0 && cnt) atomicAdd(&s_count[bit], cnt);
-        __syncthreads();
-        const uint32_t below = s_count[bit];
-        if (below < k) {     // the k-th smallest is >= cand
-            prefix = cand;
-            less = below;
+        uint32_t tau_hi, less_hi;
+        search16(16, k, tau_hi, less_hi);
+        // lower halves of the keys that tie on the upper half; every other key
+        // is parked at 0xffff, which no candidate value exceeds
+        const uint32_t base2 = launder(t0);
+#pragma unroll
+        for (int r0 = 0; r0 < kSelPackedRegs; r0 += 4) {
+#pragma unroll
+            for (int r = r0; r < r0 + 4; ++r) {
+                const uint32_t a = fetch_at(base2, 2 * r), b = fetch_at(base2, 2 * r + 1);
+                const uint32_t la = (a >> 16) == tau_hi ? (a & 0xffffu) : 0xffffu;
+                const uint32_t lb = (b >> 16) == tau_hi ? (b & 0xffffu) : 0xffffu;
+                pk[r] = la | (lb << 16);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        uint32_t tau_lo, less_lo;
+        search16(0, k - less_hi, tau_lo, less_lo);
+        prefix = (tau_hi << 16) | tau_lo;
+        less = less_hi + less_lo;
+    } else {
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t cand = prefix | (1u << bit);
+            uint32_t cnt = 0;
+            if constexpr (kInRegs) {
+#pragma unroll
+                for (int e = 0; e < E; ++e) cnt += __popcll(__ballot(regs[e] < cand));
+            } else {
+                for (int64_t e = 0; e < iters; ++e) cnt += __popcll(__ballot(fetch(e) < cand));
+            }
+            if (lane == 0 && cnt) atomicAdd(&s_count[bit], cnt);
+            __syncthreads();
+            const uint32_t below = s_count[bit];
+            if (below < k) {     // the k-th smallest is >= cand
+                prefix = cand;
+                less = below;
+            }
         }
     }
     const uint32_t tau = prefix;
@@ -87,10 +180,9 @@ void select_kernel(const uint32_t* __restrict__ norm_bits, int64_t T, uint32_t k
 
     // ---- per-wave totals, then ordered emit ---------------------------------
     uint32_t lt_w = 0, eq_w = 0;
-    auto tally = [&](uint32_t key, int64_t e) {
-        const bool valid = (t0 + e * kWaveSize) < T;
+    auto tally = [&](uint32_t key, int64_t) {
         lt_w += __popcll(__ballot(key < tau));
-        eq_w += __popcll(__ballot(valid && key == tau));
+        eq_w += __popcll(__ballot(key == tau));
     };
     if constexpr (kInRegs) {
 #pragma unroll
@@ -113,10 +205,9 @@ void select_kernel(const uint32_t* __restrict__ norm_bits, int64_t T, uint32_t k
     int32_t* out = kept_idx + head * (int64_t)k;
 
     auto emit = [&](uint32_t key, int64_t e) {
-        const int64_t t = t0 + e * kWaveSize;
-        const bool valid = t < T;
+        const uint32_t t = t0 + (uint32_t)e * kWaveSize;
         const bool is_lt = key < tau;
-        const bool is_eq = valid && key == tau;
+        const bool is_eq = key == tau;
         const uint64_t eq_mask = __ballot(is_eq);
         const bool keep = is_lt || (is_eq && (eq_base + lanes_below(eq_mask)) < need_eq);
         const uint64_t keep_mask = __ballot(keep);
@@ -136,7 +227,8 @@ void select_kernel(const uint32_t* __restrict__ norm_bits, int64_t T, uint32_t k
 template <int E>
 static void launch_select(const float* norms, int64_t n_heads, int64_t T, int64_t k, uint32_t flip,
                           int32_t* kept_idx, int32_t* kept_count, hipStream_t stream) {
-    hipLaunchKernelGGL((select_kernel<E>), dim3((unsigned)n_heads), dim3(kSelThreads), 0, stream,
+    hipLaunchKernelGGL((select_kernel<E>), dim3((unsigned)n_heads),
+                       dim3(E == -1 ? kSelPackedThreads : kSelThreads), 0, stream,
                        reinterpret_cast<const uint32_t*>(norms), T, (uint32_t)k, flip, kept_idx,
                        kept_count);
 }
@@ -155,6 +247,8 @@ l2kv_status select_dispatch(const float* norms, int64_t n_heads, int64_t T, int6
     else if (per_lane <= 16) launch_select<16>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
     else if (per_lane <= kSelMaxRegKeys)
         launch_select<32>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
+    else if (T <= (int64_t)kSelPackedThreads * 2 * kSelPackedRegs)
+        launch_select<-1>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
     else
         launch_select<0>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
     return launch_status();

@@ -5,7 +5,8 @@
 // 256-byte rows of the supported shapes), a wavefront moves 4 rows per
 // instruction, and each row group handles kUnroll consecutive output rows so
 // all index loads, then all row loads of K and V, are in flight before the
-// first store.  Dropped rows are never read.
+// first store.  Loads and stores carry the non-temporal hint (every byte is
+// touched once).  Dropped rows are never read.
 #include "l2kv_device.hpp"
 #include "l2kv_host.hpp"
 
@@ -13,7 +14,10 @@ namespace l2kv {
 
 constexpr int kCompactThreads = 256;
 constexpr int kCompactWaves = kCompactThreads / kWaveSize;
-constexpr int kCompactUnroll = 4;
+#ifndef L2KV_COMPACT_UNROLL
+#define L2KV_COMPACT_UNROLL 4
+#endif
+constexpr int kCompactUnroll = L2KV_COMPACT_UNROLL;
 constexpr int kCompactRowsPerBlock = kCompactWaves * kRowsPerWaveLoad * kCompactUnroll;  // 64
 
 // W = 32-bit words per lane slice (row bytes = 16 lanes * 4W).
@@ -45,18 +49,18 @@ void compact_kernel(const char* __restrict__ K, const char* __restrict__ V,
     }
     Words<W> kr[kCompactUnroll], vr[kCompactUnroll];
 #pragma unroll
-    for (int u = 0; u < kCompactUnroll; ++u) kr[u] = load_words<W>(K + src[u]);
+    for (int u = 0; u < kCompactUnroll; ++u) kr[u] = load_words_stream<W>(K + src[u]);
     if constexpr (HAS_V) {
 #pragma unroll
-        for (int u = 0; u < kCompactUnroll; ++u) vr[u] = load_words<W>(V + src[u]);
+        for (int u = 0; u < kCompactUnroll; ++u) vr[u] = load_words_stream<W>(V + src[u]);
     }
 #pragma unroll
     for (int u = 0; u < kCompactUnroll; ++u) {
         const int64_t j = first + u;
         if (j < k) {
             const int64_t dst = dst_head + j * kRowBytes + c * kSliceBytes;
-            store_words<W>(Kc + dst, kr[u]);
-            if constexpr (HAS_V) store_words<W>(Vc + dst, vr[u]);
+            store_words_stream<W>(Kc + dst, kr[u]);
+            if constexpr (HAS_V) store_words_stream<W>(Vc + dst, vr[u]);
         }
     }
 }

@@ -46,25 +46,9 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
 }
 
-// Streaming (non-temporal) load of a lane's slice: the cache is read once per
-// call and must not displace anything in L2.
+// K and V are read once per call: streaming loads, nothing to keep in L2.
 template <int W>
-__device__ __forceinline__ Words<W> stream_words(const char* p) {
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-    Words<W> r;
-    if constexpr (W == 2) {
-        u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
-        r.w[0] = v.x; r.w[1] = v.y;
-    } else {
-#pragma unroll
-        for (int i = 0; i < W / 4; ++i) {
-                u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p) + i);
-            r.w[4 * i + 0] = v.x; r.w[4 * i + 1] = v.y; r.w[4 * i + 2] = v.z; r.w[4 * i + 3] = v.w;
-        }
-    }
-    return r;
-}
+__device__ __forceinline__ Words<W> stream_words(const char* p) { return load_words_stream<W>(p); }
 
 // Device-scope (agent) relaxed store / load of one float.
 __device__ __forceinline__ void publish(float* p, float v) {

@@ -68,6 +68,42 @@ __device__ __forceinline__ Words<W> load_words(const void* p) {
     return r;
 }
 
+// Streaming variants: data that is read or written exactly once per call and
+// should not displace anything in the caches (non-temporal hint).
+template <int W>
+__device__ __forceinline__ Words<W> load_words_stream(const void* p) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    Words<W> r;
+    if constexpr (W == 2) {
+        u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+        r.w[0] = v.x; r.w[1] = v.y;
+    } else {
+#pragma unroll
+        for (int i = 0; i < W / 4; ++i) {
+            u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p) + i);
+            r.w[4 * i + 0] = v.x; r.w[4 * i + 1] = v.y; r.w[4 * i + 2] = v.z; r.w[4 * i + 3] = v.w;
+        }
+    }
+    return r;
+}
+
+template <int W>
+__device__ __forceinline__ void store_words_stream(void* p, const Words<W>& r) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    if constexpr (W == 2) {
+        u32x2 v = {r.w[0], r.w[1]};
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(p));
+    } else {
+#pragma unroll
+        for (int i = 0; i < W / 4; ++i) {
+            u32x4 v = {r.w[4 * i + 0], r.w[4 * i + 1], r.w[4 * i + 2], r.w[4 * i + 3]};
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p) + i);
+        }
+    }
+}
+
 template <int W>
 __device__ __forceinline__ void store_words(void* p, const Words<W>& r) {
     if constexpr (W == 2) {

@@ -3,11 +3,13 @@
 //
 // Pure HBM read stream of K.  16 lanes share a row (one 16-byte load each for
 // the 256-byte rows of the supported shapes), a wavefront covers 4 rows per
-// load instruction, and every lane issues kUnroll independent loads before the
-// first use so enough bytes are in flight.  The per-row sum follows the
-// library's fixed order: per-lane chunk left to right, then the balanced tree
-// of row16_tree_sum.  Contraction to FMA is switched off so fp32 inputs round
-// product and sum separately, like the stated order says.
+// load instruction, and every row group takes kNormUnroll consecutive rows
+// with independent non-temporal loads.  Small workgroups (32 rows) and very
+// many of them measured best: the hardware keeps enough of them in flight.
+// The per-row sum follows the library's fixed order: per-lane chunk left to
+// right, then the balanced tree of row16_tree_sum.  Contraction to FMA is
+// switched off so fp32 inputs round product and sum separately, like the stated
+// order says.
 #include "l2kv_device.hpp"
 #include "l2kv_host.hpp"
 
@@ -15,8 +17,11 @@ namespace l2kv {
 
 constexpr int kNormThreads = 256;
 constexpr int kNormWaves = kNormThreads / kWaveSize;
-constexpr int kNormUnroll = 8;                                   // rows per row group
-constexpr int kNormRowsPerBlock = kNormWaves * kRowsPerWaveLoad * kNormUnroll;  // 128
+#ifndef L2KV_NORM_UNROLL
+#define L2KV_NORM_UNROLL 2
+#endif
+constexpr int kNormUnroll = L2KV_NORM_UNROLL;                    // rows per row group
+constexpr int kNormRowsPerBlock = kNormWaves * kRowsPerWaveLoad * kNormUnroll;  // 32
 
 template <typename E, int D>
 __global__ __launch_bounds__(kNormThreads)
@@ -40,7 +45,7 @@ void norms_kernel(const char* __restrict__ K, int64_t T, int64_t head_stride_byt
     for (int u = 0; u < kNormUnroll; ++u) {
         int64_t row = first + u;
         row = row < T ? row : T - 1;      // tail: re-read the last row, result unused
-        raw[u] = load_words<S::kWords>(head_base + row * S::kRowBytes + c * S::kBytes);
+        raw[u] = load_words_stream<S::kWords>(head_base + row * S::kRowBytes + c * S::kBytes);
     }
 
     float mine = 0.f;

@@ -13,6 +13,8 @@ Functions, each following the passage named in the C source:
 * ``compact(X, idx)``             -- gather of kept rows ("and the corresponding values")
 * ``decode_attn(Q, Kc, Vc, ...)`` -- single-query softmax attention (Eq. 2 / Eq. 4)
 * ``compress(K, V, dtype, r)``    -- the three compression steps in sequence
+* ``StreamHead``                  -- one (sequence, head) cache under streaming
+                                     eviction (Sec. 4, language-modelling setting)
 """
 from __future__ import annotations
 
@@ -70,6 +72,13 @@ def _load():
         lib.l2kv_oracle_decode_attn.argtypes = [
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_int, c.c_int32, c.c_int32,
             c.c_int32, c.c_int64, c.c_int32, c.c_int64, c.c_double, c.c_void_p]
+        lib.l2kv_oracle_stream_append.restype = c.c_int
+        lib.l2kv_oracle_stream_append.argtypes = [
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int,
+            c.c_int32, c.c_void_p, c.c_void_p, c.c_int32]
+        lib.l2kv_oracle_stream_evict.restype = c.c_int
+        lib.l2kv_oracle_stream_evict.argtypes = [
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int, c.c_int32]
         _lib = lib
     return _lib
 
@@ -163,3 +172,56 @@ def compress(K: np.ndarray, V: np.ndarray, dtype, keep_ratio: float,
         k = keep_count(K.shape[-2], keep_ratio)
     idx = select(n32, k, mode)
     return n32, n64, idx, compact(K, idx), compact(V, idx)
+
+
+class StreamHead:
+    """One (sequence, head) slot cache under streaming eviction: append a token,
+    attend, then drop highest-norm tokens until the budget holds (Sec. 4,
+    "Language Modelling Tasks").  Slots carry K/V rows, the fp32 squared norm
+    and the original token id; slot order has no meaning."""
+
+    def __init__(self, capacity: int, D: int, dtype):
+        self.dtype, self.D, self.capacity = dtype, int(D), int(capacity)
+        npdt = _np_dtype(dtype)
+        self.K = np.zeros((capacity, D), dtype=npdt)
+        self.V = np.zeros((capacity, D), dtype=npdt)
+        self.norms = np.zeros(capacity, dtype=np.float32)
+        self.pos = np.full(capacity, -1, dtype=np.int32)
+        self._len = ctypes.c_int32(0)
+
+    def __len__(self) -> int:
+        return int(self._len.value)
+
+    def load(self, K: np.ndarray, V: np.ndarray, n32: np.ndarray, pos: np.ndarray) -> None:
+        """Start from an already compressed cache (rows, norms, token ids)."""
+        n = K.shape[0]
+        assert n <= self.capacity
+        self.K[:n], self.V[:n], self.norms[:n], self.pos[:n] = K, V, n32, pos
+        self._len.value = n
+
+    def append(self, k_new: np.ndarray, v_new: np.ndarray, token_id: int) -> None:
+        k_new = _check(k_new, self.dtype)
+        v_new = _check(v_new, self.dtype)
+        rc = _load().l2kv_oracle_stream_append(
+            self.K.ctypes.data, self.V.ctypes.data, self.norms.ctypes.data, self.pos.ctypes.data,
+            ctypes.byref(self._len), self.capacity, _DT[self.dtype], self.D,
+            k_new.ctypes.data, v_new.ctypes.data, int(token_id))
+        if rc != 0:
+            raise ValueError("stream append: cache full or bad shape")
+
+    def evict_to(self, budget: int) -> int:
+        return int(_load().l2kv_oracle_stream_evict(
+            self.K.ctypes.data, self.V.ctypes.data, self.norms.ctypes.data, self.pos.ctypes.data,
+            ctypes.byref(self._len), int(budget), _DT[self.dtype], self.D))
+
+    def attend(self, q: np.ndarray, scale: float = 0.0) -> np.ndarray:
+        """q ``[G, D]`` (the query heads sharing this KV head) -> ``[G, D]`` float32."""
+        n = len(self)
+        return decode_attn(np.ascontiguousarray(q)[None], self.K[None, None, :n], self.V[None, None, :n],
+                           self.dtype, scale)[0]
+
+    def kept(self):
+        """(token ids ascending, K rows, V rows, norms) of the occupied slots."""
+        n = len(self)
+        order = np.argsort(self.pos[:n], kind="stable")
+        return self.pos[:n][order], self.K[:n][order], self.V[:n][order], self.norms[:n][order]

@@ -265,3 +265,66 @@ int l2kv_oracle_decode_attn(const void *Q, const void *Kc, const void *Vc,
     free(acc);
     return 0;
 }
+
+/* ------------------------------------------------------------------------
+ * Streaming eviction (Sec. 4, "Language Modelling Tasks": the cache grows to a
+ * pre-defined length, after which the tokens with the highest L2 norm are
+ * discarded).  One (sequence, head) at a time; the cache is a set of slots,
+ * slot j holding the key/value rows, the fp32 squared norm (fixed summation
+ * order above) and the original token id of one kept token.
+ *
+ * Eviction order is the reverse of the keep order of l2kv_oracle_select: the
+ * slot with the LARGEST (norm bits, token id) goes first, so among equal norms
+ * the later token is dropped and the kept set is always "the lowest-norm
+ * tokens, ties to the lower token id".  The hole is filled with the last slot
+ * (the slot order carries no meaning; tests compare token-id sets).
+ * ------------------------------------------------------------------------ */
+
+/* Append one token: rows copied to slot *len, norm and id recorded, *len += 1. */
+int l2kv_oracle_stream_append(void *K, void *V, float *norms, int32_t *pos, int32_t *len,
+                              int32_t capacity, int dtype, int32_t D, const void *k_new,
+                              const void *v_new, int32_t token_id)
+{
+    if (*len >= capacity || D <= 0 || D % 16 != 0)
+        return -1;
+    size_t rb = (size_t)D * (dtype == ORACLE_BF16 ? 2 : 4);
+    memcpy((char *)K + (size_t)*len * rb, k_new, rb);
+    memcpy((char *)V + (size_t)*len * rb, v_new, rb);
+    norms[*len] = row_norm_f32(k_new, dtype, D);
+    pos[*len] = token_id;
+    *len += 1;
+    return 0;
+}
+
+/* While more than `budget` slots are occupied, drop the slot with the largest
+ * (norm bits, token id) and move the last slot into its place.
+ * Returns the number of evictions. */
+int l2kv_oracle_stream_evict(void *K, void *V, float *norms, int32_t *pos, int32_t *len,
+                             int32_t budget, int dtype, int32_t D)
+{
+    size_t rb = (size_t)D * (dtype == ORACLE_BF16 ? 2 : 4);
+    int evicted = 0;
+    if (budget < 0)
+        budget = 0;
+    while (*len > budget) {
+        int32_t worst = 0;
+        uint64_t worst_key = 0;
+        for (int32_t j = 0; j < *len; ++j) {
+            uint64_t key = ((uint64_t)float_bits(norms[j]) << 32) | (uint64_t)(uint32_t)pos[j];
+            if (j == 0 || key > worst_key) {
+                worst_key = key;
+                worst = j;
+            }
+        }
+        int32_t last = *len - 1;
+        if (worst != last) {
+            memcpy((char *)K + (size_t)worst * rb, (char *)K + (size_t)last * rb, rb);
+            memcpy((char *)V + (size_t)worst * rb, (char *)V + (size_t)last * rb, rb);
+            norms[worst] = norms[last];
+            pos[worst] = pos[last];
+        }
+        *len = last;
+        ++evicted;
+    }
+    return evicted;
+}

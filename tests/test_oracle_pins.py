@@ -417,3 +417,74 @@ def test_kept_set_ignores_values_and_queries_and_keep1_is_full_attention():
     _, _, _, K1, V1 = oracle.compress(Kn, Vn, "f32", 1.0)
     np.testing.assert_array_equal(oracle.decode_attn(Q, K1, V1, "f32"),
                                   oracle.decode_attn(Q, Kn, Vn, "f32"))
+
+
+# ------------------------------------------------------------ streaming eviction
+def _stream_tokens(rng, T, D, dt, ties=False):
+    K = rng.standard_normal((T, D)).astype(np.float32) * np.exp(0.5 * rng.standard_normal((T, 1))).astype(np.float32)
+    if ties:
+        K[::3] = K[0]                                   # many equal norms
+    V = rng.standard_normal((T, D)).astype(np.float32)
+    if dt == "bf16":
+        return bf16_bits(K), bf16_bits(V)
+    return K, V
+
+
+@pytest.mark.parametrize("dt,D", [("f32", 64), ("bf16", 128)])
+@pytest.mark.parametrize("ties", [False, True])
+def test_stream_fixed_budget_equals_one_shot_selection(dt, D, ties):
+    # classic streaming top-k: with a fixed budget the kept token set after every step is the
+    # one-shot selection over all tokens seen so far (lowest (norm bits, id), exact count)
+    rng = np.random.default_rng(5 + D)
+    T, budget = 90, 17
+    K, V = _stream_tokens(rng, T, D, dt, ties)
+    n32, _ = oracle.norms(K[None], dt)
+    head = oracle.StreamHead(budget + 1, D, dt)
+    for t in range(T):
+        head.append(K[t], V[t], t)
+        assert head.evict_to(budget) == (1 if t >= budget else 0)
+        ids, Kk, Vk, nk = head.kept()
+        want = oracle.select(n32[:, : t + 1], min(budget, t + 1))[0]
+        assert np.array_equal(ids, want)
+        assert np.array_equal(Kk, K[want]) and np.array_equal(Vk, V[want])
+        assert np.array_equal(nk.view(np.uint32), n32[0, want].view(np.uint32))
+
+
+def test_stream_eviction_drops_largest_norm_then_largest_id():
+    D = 16
+    head = oracle.StreamHead(8, D, "f32")
+    vals = [2.0, 3.0, 1.0, 3.0, 0.5, 3.0]              # squared norms 4, 9, 1, 9, .25, 9
+    for t, v in enumerate(vals):
+        row = np.zeros(D, np.float32)
+        row[t] = v
+        head.append(row, row, t)
+    assert head.evict_to(5) == 1 and list(head.kept()[0]) == [0, 1, 2, 3, 4]      # id 5 (norm 9, latest) first
+    assert head.evict_to(3) == 2 and list(head.kept()[0]) == [0, 2, 4]            # then ids 3 and 1
+    assert head.evict_to(3) == 0
+    assert head.evict_to(0) == 3 and len(head) == 0
+
+
+def test_stream_growing_budget_and_attention():
+    # budget(t) = keep_count(L0 + t, r): start from a compressed prompt, decode 40 steps
+    rng = np.random.default_rng(77)
+    D, dt, L0, r, steps, G = 64, "f32", 50, 0.5, 40, 2
+    K, V = _stream_tokens(rng, L0 + steps, D, dt)
+    n32, _ = oracle.norms(K[None], dt)
+    k0 = oracle.keep_count(L0, r)
+    idx0 = oracle.select(n32[:, :L0], k0)[0]
+    cap = oracle.keep_count(L0 + steps, r) + 1
+    head = oracle.StreamHead(cap, D, dt)
+    head.load(K[idx0], V[idx0], n32[0, idx0], idx0.astype(np.int32))
+    for t in range(steps):
+        tok = L0 + t
+        head.append(K[tok], V[tok], tok)
+        q = rng.standard_normal((G, D)).astype(np.float32)
+        out = head.attend(q)
+        ids = head.kept()[0]
+        # attention over the slots equals attention over the same tokens in any order
+        want = oracle.decode_attn(q[None], K[None, None, ids], V[None, None, ids], dt)[0]
+        np.testing.assert_allclose(out, want, atol=1e-6)
+        head.evict_to(oracle.keep_count(tok + 1, r))
+        assert len(head) == oracle.keep_count(tok + 1, r)
+        # evicting is monotone: a token once dropped never comes back, the newest may be dropped at once
+        assert set(head.kept()[0]) <= set(ids)

@@ -172,6 +172,112 @@ l2kv_status l2kv_decode_attn_splits(const void* Q, const void* Kc, const void* V
 int32_t l2kv_decode_max_splits(int64_t kv_len);
 size_t  l2kv_decode_workspace_bytes(int32_t B, int32_t Hq, int64_t kv_len, int32_t D);
 
+/* ------------------------------------------------------------------------
+ * Ragged batches and streaming eviction.
+ *
+ * Sec. 4 ("Language Modelling Tasks"): the cache is allowed to grow to a
+ * pre-defined length, after which the tokens with the highest key norm are
+ * discarded.  A batch of sequences of different lengths is held ragged:
+ *
+ *   prompt tensors   K, V [n_planes][total_tokens][D], norms [n_planes][total_tokens];
+ *                    sequence s = rows in_offsets[s] .. in_offsets[s+1]-1 of every plane
+ *   slot cache       Kc, Vc [n_planes][total_slots][D], norms_c [n_planes][total_slots] fp32,
+ *                    pos_c [n_planes][total_slots] int32 (original token id of each slot);
+ *                    sequence s owns slots slot_offsets[s] .. slot_offsets[s+1]-1 of every
+ *                    plane, of which the first lens[s] are occupied (same count in all planes)
+ *
+ * n_planes = layers x KV heads (plane = layer*Hkv + head).  All offset arrays
+ * are DEVICE int64 [n_seq+1], ascending, first entry 0; lens / budgets /
+ * token_ids are DEVICE int32 [n_seq].  Their contents cannot be checked on the
+ * host: the kernels clamp what they read so that nothing is accessed outside
+ * the buffers described by total_tokens / total_slots, but inconsistent
+ * arrays give meaningless results.  Slot order inside a sequence carries no
+ * meaning (attention is order-free); after l2kv_compact_ragged it is ascending
+ * token order, evictions then move the last slot into the hole.
+ * ------------------------------------------------------------------------ */
+
+/*
+ * Selection on a ragged batch: for every plane and sequence, the
+ * k_s = out_offsets[s+1]-out_offsets[s] positions with the lowest (norm bits,
+ * position) among its T_s = in_offsets[s+1]-in_offsets[s] tokens (k_s is capped
+ * at T_s; the caller normally sets it with l2kv_keep_count(T_s, keep_ratio)).
+ * Positions are relative to the sequence start, ascending.
+ *   kept_idx out: [n_planes][total_kept] int32, sequence s at out_offsets[s]
+ *   max_len     : an upper bound of all T_s (chooses the kernel variant; tokens
+ *                 of a sequence beyond it would be ignored)
+ * Errors: NULL, SHAPE, ALIGN, LAUNCH.
+ */
+l2kv_status l2kv_select_ragged(const float* norms, int32_t n_planes, int32_t n_seq,
+                               int64_t total_tokens, const int64_t* in_offsets,
+                               const int64_t* out_offsets, int64_t total_kept, int64_t max_len,
+                               l2kv_mode mode, int32_t* kept_idx, void* stream);
+
+/*
+ * Compaction of a ragged batch into the slot cache: slot j of sequence s gets
+ * row kept_idx[..][j] of that sequence (K, V, its norm, and the position as
+ * token id).  Sets up the cache that l2kv_stream_* and l2kv_decode_attn_ragged
+ * work on; lens[s] = k_s is the caller's to fill.  k_s is capped at the
+ * sequence's slot capacity.  max_kept: an upper bound of all k_s.
+ * Errors: NULL, SHAPE, DTYPE, ALIGN, LAUNCH.
+ */
+l2kv_status l2kv_compact_ragged(const void* K, const void* V, const float* norms, l2kv_dtype dt,
+                                const int32_t* kept_idx, int32_t n_planes, int32_t n_seq,
+                                int64_t total_tokens, const int64_t* in_offsets,
+                                const int64_t* out_offsets, int64_t total_kept, int64_t max_kept,
+                                const int64_t* slot_offsets, int64_t total_slots, int32_t D,
+                                void* Kc, void* Vc, float* norms_c, int32_t* pos_c, void* stream);
+
+/*
+ * Append the current token of every sequence (Eq. 4: its K_t, V_t join the
+ * cache before the query attends): Knew, Vnew [n_layers][n_seq][Hkv][D] go to
+ * slot lens_in[s] of sequence s in plane layer*Hkv+head, with the squared key
+ * norm (same fixed summation order as l2kv_norms) and token_ids[s].
+ * lens_out[s] = lens_in[s] + 1; a sequence whose slots are all occupied is left
+ * unchanged (lens_out[s] = lens_in[s]).  lens_out must not be lens_in.
+ * Errors: NULL, SHAPE, DTYPE, ALIGN, LAUNCH.
+ */
+l2kv_status l2kv_stream_append(const void* Knew, const void* Vnew, l2kv_dtype dt, int32_t n_layers,
+                               int32_t n_seq, int32_t Hkv, int32_t D, const int32_t* token_ids,
+                               const int64_t* slot_offsets, int64_t total_slots,
+                               const int32_t* lens_in, int32_t* lens_out, void* Kc, void* Vc,
+                               float* norms_c, int32_t* pos_c, void* stream);
+
+/*
+ * Evict down to the budget: in every plane, while sequence s holds more than
+ * budgets[s] slots, the slot with the largest (norm bits, token id) is dropped
+ * (among equal norms the later token goes first -- the reverse of the keep
+ * order of l2kv_select) and the last slot is moved into its place.
+ * lens_out[s] = min(lens_in[s], budgets[s]).  lens_out must not be lens_in.
+ * With a fixed budget the kept token set equals l2kv_select over all tokens
+ * seen; with budgets[s] = l2kv_keep_count(tokens seen, keep_ratio) it is the
+ * keep_ratio "enforced incrementally".
+ * Errors: NULL, SHAPE, DTYPE, ALIGN, LAUNCH.
+ */
+l2kv_status l2kv_stream_evict(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, int32_t D,
+                              const int64_t* slot_offsets, int64_t total_slots,
+                              const int32_t* lens_in, const int32_t* budgets, int32_t* lens_out,
+                              void* Kc, void* Vc, float* norms_c, int32_t* pos_c, void* stream);
+
+/*
+ * Decode attention over ONE layer of the slot cache: Q [n_seq][Hq][D]; Kc, Vc
+ * point at that layer's Hkv planes ([Hkv][total_slots][D]); sequence s attends
+ * to its lens[s] occupied slots (0 slots give a zero output row).
+ *   max_len : an upper bound of all lens[s] (sizes the decomposition and the
+ *             workspace; rows beyond it are still attended to)
+ *   n_splits: 0 = library default
+ *   workspace: l2kv_decode_ragged_workspace_bytes(n_seq, Hq, max_len, D) bytes,
+ *              same zero-before-first-use contract as l2kv_decode_attn
+ * Errors: as l2kv_decode_attn.
+ */
+l2kv_status l2kv_decode_attn_ragged(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt,
+                                    int32_t n_seq, int32_t Hq, int32_t Hkv, int32_t D,
+                                    const int32_t* lens, const int64_t* slot_offsets,
+                                    int64_t total_slots, int64_t max_len, float scale,
+                                    int32_t n_splits, float* O, void* workspace,
+                                    size_t workspace_bytes, void* stream);
+
+size_t l2kv_decode_ragged_workspace_bytes(int32_t n_seq, int32_t Hq, int64_t max_len, int32_t D);
+
 /* Static, NUL-terminated description of a status code. */
 const char* l2kv_status_string(l2kv_status s);
 

@@ -41,6 +41,23 @@ SIGNATURES = {
                                           C.c_void_p]),
     "l2kv_decode_max_splits": (C.c_int32, [C.c_int64]),
     "l2kv_decode_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int64, C.c_int32]),
+    "l2kv_select_ragged": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
+                                     C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p]),
+    "l2kv_compact_ragged": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int32,
+                                      C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                      C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_void_p]),
+    "l2kv_stream_append": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32, C.c_int32,
+                                     C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "l2kv_stream_evict": (C.c_int, [C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int64,
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_void_p]),
+    "l2kv_decode_attn_ragged": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32,
+                                          C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
+                                          C.c_float, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
+                                          C.c_void_p]),
+    "l2kv_decode_ragged_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int64, C.c_int32]),
     "l2kv_status_string": (C.c_char_p, [C.c_int]),
     "l2kv_version": (C.c_int32, []),
 }
@@ -207,3 +224,97 @@ def l2kv_decode_attn_splits(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor,
                                            D, n * D, float(scale), int(n_splits), _ptr(O),
                                            _ptr(workspace), ws_bytes, _stream(stream))
         _check("l2kv_decode_attn_splits", st)
+
+
+# ------------------------------------------------- ragged batches / streaming
+def l2kv_decode_ragged_workspace_bytes(n_seq: int, Hq: int, max_len: int, D: int) -> int:
+    return int(lib().l2kv_decode_ragged_workspace_bytes(int(n_seq), int(Hq), int(max_len), int(D)))
+
+
+def _i64(t: torch.Tensor, n: int) -> None:
+    assert t.dtype == torch.int64 and t.numel() == n
+
+
+def _i32(t: torch.Tensor, n: int) -> None:
+    assert t.dtype == torch.int32 and t.numel() == n
+
+
+def l2kv_select_ragged(norms: torch.Tensor, in_offsets: torch.Tensor, out_offsets: torch.Tensor,
+                       max_len: int, kept_idx: torch.Tensor, mode: int = L2KV_KEEP_LOWEST,
+                       stream=None) -> None:
+    """norms ``[n_planes, total_tokens]`` -> kept_idx ``[n_planes, total_kept]`` (positions relative
+    to each sequence start); offsets are device int64 ``[n_seq + 1]``."""
+    _dev(norms, in_offsets, out_offsets, kept_idx)
+    n_planes, total = norms.shape
+    n_seq = in_offsets.numel() - 1
+    _i64(out_offsets, n_seq + 1)
+    assert norms.dtype == torch.float32 and kept_idx.dtype == torch.int32 and kept_idx.shape[0] == n_planes
+    _check("l2kv_select_ragged", lib().l2kv_select_ragged(
+        _ptr(norms), n_planes, n_seq, total, _ptr(in_offsets), _ptr(out_offsets), kept_idx.shape[1],
+        int(max_len), int(mode), _ptr(kept_idx), _stream(stream)))
+
+
+def l2kv_compact_ragged(K: torch.Tensor, V: torch.Tensor, norms: torch.Tensor, kept_idx: torch.Tensor,
+                        in_offsets: torch.Tensor, out_offsets: torch.Tensor, max_kept: int,
+                        slot_offsets: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor,
+                        norms_c: torch.Tensor, pos_c: torch.Tensor, stream=None) -> None:
+    """K, V ``[n_planes, total_tokens, D]`` -> slot cache Kc, Vc ``[n_planes, total_slots, D]``,
+    norms_c, pos_c ``[n_planes, total_slots]``."""
+    _dev(K, V, norms, kept_idx, in_offsets, out_offsets, slot_offsets, Kc, Vc, norms_c, pos_c)
+    n_planes, total, D = K.shape
+    n_seq = in_offsets.numel() - 1
+    total_slots = Kc.shape[1]
+    assert V.shape == K.shape and Kc.shape == (n_planes, total_slots, D) and Vc.shape == Kc.shape
+    assert norms.shape == (n_planes, total) and norms_c.shape == (n_planes, total_slots)
+    assert pos_c.shape == (n_planes, total_slots) and pos_c.dtype == torch.int32
+    _i64(out_offsets, n_seq + 1)
+    _i64(slot_offsets, n_seq + 1)
+    _check("l2kv_compact_ragged", lib().l2kv_compact_ragged(
+        _ptr(K), _ptr(V), _ptr(norms), _dtype_code(K), _ptr(kept_idx), n_planes, n_seq, total,
+        _ptr(in_offsets), _ptr(out_offsets), kept_idx.shape[1], int(max_kept), _ptr(slot_offsets),
+        total_slots, D, _ptr(Kc), _ptr(Vc), _ptr(norms_c), _ptr(pos_c), _stream(stream)))
+
+
+def l2kv_stream_append(Knew: torch.Tensor, Vnew: torch.Tensor, token_ids: torch.Tensor,
+                       slot_offsets: torch.Tensor, lens_in: torch.Tensor, lens_out: torch.Tensor,
+                       Kc: torch.Tensor, Vc: torch.Tensor, norms_c: torch.Tensor, pos_c: torch.Tensor,
+                       stream=None) -> None:
+    """Knew, Vnew ``[n_layers, n_seq, Hkv, D]`` -> next free slot of every sequence."""
+    _dev(Knew, Vnew, token_ids, slot_offsets, lens_in, lens_out, Kc, Vc, norms_c, pos_c)
+    n_layers, n_seq, Hkv, D = Knew.shape
+    n_planes, total_slots, Dc = Kc.shape
+    assert Vnew.shape == Knew.shape and n_planes == n_layers * Hkv and Dc == D and Vc.shape == Kc.shape
+    _i32(token_ids, n_seq), _i32(lens_in, n_seq), _i32(lens_out, n_seq), _i64(slot_offsets, n_seq + 1)
+    _check("l2kv_stream_append", lib().l2kv_stream_append(
+        _ptr(Knew), _ptr(Vnew), _dtype_code(Knew), n_layers, n_seq, Hkv, D, _ptr(token_ids),
+        _ptr(slot_offsets), total_slots, _ptr(lens_in), _ptr(lens_out), _ptr(Kc), _ptr(Vc),
+        _ptr(norms_c), _ptr(pos_c), _stream(stream)))
+
+
+def l2kv_stream_evict(slot_offsets: torch.Tensor, lens_in: torch.Tensor, budgets: torch.Tensor,
+                      lens_out: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor,
+                      norms_c: torch.Tensor, pos_c: torch.Tensor, stream=None) -> None:
+    _dev(slot_offsets, lens_in, budgets, lens_out, Kc, Vc, norms_c, pos_c)
+    n_planes, total_slots, D = Kc.shape
+    n_seq = lens_in.numel()
+    _i32(lens_in, n_seq), _i32(budgets, n_seq), _i32(lens_out, n_seq), _i64(slot_offsets, n_seq + 1)
+    _check("l2kv_stream_evict", lib().l2kv_stream_evict(
+        _dtype_code(Kc), n_planes, n_seq, D, _ptr(slot_offsets), total_slots, _ptr(lens_in),
+        _ptr(budgets), _ptr(lens_out), _ptr(Kc), _ptr(Vc), _ptr(norms_c), _ptr(pos_c), _stream(stream)))
+
+
+def l2kv_decode_attn_ragged(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, lens: torch.Tensor,
+                            slot_offsets: torch.Tensor, max_len: int, O: torch.Tensor,
+                            workspace: torch.Tensor, scale: float = 0.0, n_splits: int = 0,
+                            stream=None) -> None:
+    """Q ``[n_seq, Hq, D]``, Kc/Vc ``[Hkv, total_slots, D]`` (one layer) -> O ``[n_seq, Hq, D]``."""
+    _dev(Q, Kc, Vc, lens, slot_offsets, O, workspace)
+    n_seq, Hq, D = Q.shape
+    Hkv, total_slots, Dc = Kc.shape
+    assert Dc == D and Vc.shape == Kc.shape and Kc.dtype == Q.dtype == Vc.dtype
+    assert O.dtype == torch.float32 and O.numel() == n_seq * Hq * D
+    _i32(lens, n_seq), _i64(slot_offsets, n_seq + 1)
+    _check("l2kv_decode_attn_ragged", lib().l2kv_decode_attn_ragged(
+        _ptr(Q), _ptr(Kc), _ptr(Vc), _dtype_code(Q), n_seq, Hq, Hkv, D, _ptr(lens), _ptr(slot_offsets),
+        total_slots, int(max_len), float(scale), int(n_splits), _ptr(O), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)))

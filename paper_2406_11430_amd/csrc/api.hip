@@ -148,8 +148,8 @@ l2kv_status l2kv_decode_attn_splits(const void* Q, const void* Kc, const void* V
         return L2KV_ERR_ALIGN;
     const float s = scale > 0.f ? scale : 1.0f / std::sqrt(static_cast<float>(D));
     const DecodePlan plan = decode_plan(B, Hkv, kv_len, n_splits);
-    return decode_dispatch(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, s, plan, O,
-                           workspace, static_cast<hipStream_t>(stream));
+    return decode_dispatch(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, nullptr, nullptr, s,
+                           plan, O, workspace, static_cast<hipStream_t>(stream));
 }
 
 l2kv_status l2kv_decode_attn(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt, int32_t B,
@@ -158,6 +158,119 @@ l2kv_status l2kv_decode_attn(const void* Q, const void* Kc, const void* Vc, l2kv
                              size_t workspace_bytes, void* stream) {
     return l2kv_decode_attn_splits(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, scale, 0, O,
                                    workspace, workspace_bytes, stream);
+}
+
+/* ---- ragged batches and the streaming slot cache ------------------------- */
+
+l2kv_status l2kv_select_ragged(const float* norms, int32_t n_planes, int32_t n_seq,
+                               int64_t total_tokens, const int64_t* in_offsets,
+                               const int64_t* out_offsets, int64_t total_kept, int64_t max_len,
+                               l2kv_mode mode, int32_t* kept_idx, void* stream) {
+    if (norms == nullptr || in_offsets == nullptr || out_offsets == nullptr || kept_idx == nullptr)
+        return L2KV_ERR_NULL;
+    if (n_planes <= 0 || n_seq <= 0 || total_tokens <= 0 || total_tokens > kMaxTokens ||
+        total_kept <= 0 || total_kept > total_tokens || max_len <= 0 || max_len > total_tokens)
+        return L2KV_ERR_SHAPE;
+    if (mode != L2KV_KEEP_LOWEST && mode != L2KV_KEEP_HIGHEST) return L2KV_ERR_SHAPE;
+    if (!aligned(norms, 4) || !aligned(kept_idx, 4) || !aligned(in_offsets, 8) || !aligned(out_offsets, 8))
+        return L2KV_ERR_ALIGN;
+    return select_ragged_dispatch(norms, n_planes, n_seq, total_tokens, in_offsets, out_offsets,
+                                  total_kept, max_len, mode, kept_idx, static_cast<hipStream_t>(stream));
+}
+
+l2kv_status l2kv_compact_ragged(const void* K, const void* V, const float* norms, l2kv_dtype dt,
+                                const int32_t* kept_idx, int32_t n_planes, int32_t n_seq,
+                                int64_t total_tokens, const int64_t* in_offsets,
+                                const int64_t* out_offsets, int64_t total_kept, int64_t max_kept,
+                                const int64_t* slot_offsets, int64_t total_slots, int32_t D, void* Kc,
+                                void* Vc, float* norms_c, int32_t* pos_c, void* stream) {
+    if (K == nullptr || V == nullptr || norms == nullptr || kept_idx == nullptr || in_offsets == nullptr ||
+        out_offsets == nullptr || slot_offsets == nullptr || Kc == nullptr || Vc == nullptr ||
+        norms_c == nullptr || pos_c == nullptr)
+        return L2KV_ERR_NULL;
+    if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
+    if (n_planes <= 0 || n_seq <= 0 || total_tokens <= 0 || total_tokens > kMaxTokens ||
+        total_kept <= 0 || total_kept > total_tokens || max_kept <= 0 || max_kept > total_kept ||
+        total_slots <= 0 || total_slots > kMaxTokens || !dim_ok(D))
+        return L2KV_ERR_SHAPE;
+    if (!aligned(K, 16) || !aligned(V, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(norms, 4) ||
+        !aligned(norms_c, 4) || !aligned(pos_c, 4) || !aligned(kept_idx, 4) || !aligned(in_offsets, 8) ||
+        !aligned(out_offsets, 8) || !aligned(slot_offsets, 8))
+        return L2KV_ERR_ALIGN;
+    return compact_ragged_dispatch(K, V, norms, dt, kept_idx, n_planes, n_seq, total_tokens, in_offsets,
+                                   out_offsets, total_kept, max_kept, slot_offsets, total_slots, D, Kc,
+                                   Vc, norms_c, pos_c, static_cast<hipStream_t>(stream));
+}
+
+l2kv_status l2kv_stream_append(const void* Knew, const void* Vnew, l2kv_dtype dt, int32_t n_layers,
+                               int32_t n_seq, int32_t Hkv, int32_t D, const int32_t* token_ids,
+                               const int64_t* slot_offsets, int64_t total_slots, const int32_t* lens_in,
+                               int32_t* lens_out, void* Kc, void* Vc, float* norms_c, int32_t* pos_c,
+                               void* stream) {
+    if (Knew == nullptr || Vnew == nullptr || token_ids == nullptr || slot_offsets == nullptr ||
+        lens_in == nullptr || lens_out == nullptr || Kc == nullptr || Vc == nullptr ||
+        norms_c == nullptr || pos_c == nullptr)
+        return L2KV_ERR_NULL;
+    if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
+    if (n_layers <= 0 || n_seq <= 0 || Hkv <= 0 || total_slots <= 0 || total_slots > kMaxTokens || !dim_ok(D))
+        return L2KV_ERR_SHAPE;
+    if (lens_in == lens_out) return L2KV_ERR_SHAPE;           // workgroups read lens_in while one writes lens_out
+    if (!aligned(Knew, 16) || !aligned(Vnew, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) ||
+        !aligned(norms_c, 4) || !aligned(pos_c, 4) || !aligned(token_ids, 4) || !aligned(lens_in, 4) ||
+        !aligned(lens_out, 4) || !aligned(slot_offsets, 8))
+        return L2KV_ERR_ALIGN;
+    return stream_append_dispatch(Knew, Vnew, dt, n_layers, n_seq, Hkv, D, token_ids, slot_offsets,
+                                  total_slots, lens_in, lens_out, Kc, Vc, norms_c, pos_c,
+                                  static_cast<hipStream_t>(stream));
+}
+
+l2kv_status l2kv_stream_evict(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, int32_t D,
+                              const int64_t* slot_offsets, int64_t total_slots, const int32_t* lens_in,
+                              const int32_t* budgets, int32_t* lens_out, void* Kc, void* Vc,
+                              float* norms_c, int32_t* pos_c, void* stream) {
+    if (slot_offsets == nullptr || lens_in == nullptr || budgets == nullptr || lens_out == nullptr ||
+        Kc == nullptr || Vc == nullptr || norms_c == nullptr || pos_c == nullptr)
+        return L2KV_ERR_NULL;
+    if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
+    if (n_planes <= 0 || n_seq <= 0 || total_slots <= 0 || total_slots > kMaxTokens || !dim_ok(D))
+        return L2KV_ERR_SHAPE;
+    if (lens_in == lens_out) return L2KV_ERR_SHAPE;
+    if (!aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(norms_c, 4) || !aligned(pos_c, 4) ||
+        !aligned(lens_in, 4) || !aligned(lens_out, 4) || !aligned(budgets, 4) || !aligned(slot_offsets, 8))
+        return L2KV_ERR_ALIGN;
+    return stream_evict_dispatch(dt, n_planes, n_seq, D, slot_offsets, total_slots, lens_in, budgets,
+                                 lens_out, Kc, Vc, norms_c, pos_c, static_cast<hipStream_t>(stream));
+}
+
+size_t l2kv_decode_ragged_workspace_bytes(int32_t n_seq, int32_t Hq, int64_t max_len, int32_t D) {
+    return l2kv_decode_workspace_bytes(n_seq, Hq, max_len, D);
+}
+
+l2kv_status l2kv_decode_attn_ragged(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt,
+                                    int32_t n_seq, int32_t Hq, int32_t Hkv, int32_t D,
+                                    const int32_t* lens, const int64_t* slot_offsets,
+                                    int64_t total_slots, int64_t max_len, float scale, int32_t n_splits,
+                                    float* O, void* workspace, size_t workspace_bytes, void* stream) {
+    if (Q == nullptr || Kc == nullptr || Vc == nullptr || O == nullptr || lens == nullptr ||
+        slot_offsets == nullptr)
+        return L2KV_ERR_NULL;
+    if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
+    if (n_seq <= 0 || Hq <= 0 || Hkv <= 0 || max_len <= 0 || total_slots <= 0 ||
+        total_slots > kMaxTokens || max_len > total_slots || !dim_ok(D))
+        return L2KV_ERR_SHAPE;
+    if (Hq % Hkv != 0 || Hq / Hkv > 8) return L2KV_ERR_SHAPE;
+    if (static_cast<int64_t>(n_seq) * Hkv > 65535) return L2KV_ERR_SHAPE;
+    if (n_splits < 0 || n_splits > decode_max_splits(max_len)) return L2KV_ERR_SHAPE;
+    if (!std::isfinite(scale)) return L2KV_ERR_SHAPE;
+    if (workspace == nullptr || workspace_bytes < l2kv_decode_workspace_bytes(n_seq, Hq, max_len, D))
+        return L2KV_ERR_WORKSPACE;
+    if (!aligned(Q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(O, 4) ||
+        !aligned(workspace, 16) || !aligned(lens, 4) || !aligned(slot_offsets, 8))
+        return L2KV_ERR_ALIGN;
+    const float s = scale > 0.f ? scale : 1.0f / std::sqrt(static_cast<float>(D));
+    const DecodePlan plan = decode_plan_ragged(n_seq, Hkv, max_len, n_splits);
+    return decode_dispatch(Q, Kc, Vc, dt, n_seq, Hq, Hkv, max_len, D, total_slots * static_cast<int64_t>(D),
+                           lens, slot_offsets, s, plan, O, workspace, static_cast<hipStream_t>(stream));
 }
 
 const char* l2kv_status_string(l2kv_status s) {

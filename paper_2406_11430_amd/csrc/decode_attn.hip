@@ -103,8 +103,9 @@ __device__ __forceinline__ void load_tile_clamped(Tile<E, D>& t, const char* Kh,
 template <typename E, int D, int G>
 __global__ __launch_bounds__(kDecThreads)
 void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
-                   const char* __restrict__ Vc, int Hkv, int64_t kv_len,
-                   int64_t head_stride_bytes, int n_splits,
+                   const char* __restrict__ Vc, int Hkv, int64_t kv_len_uniform,
+                   int64_t head_stride_bytes, const int32_t* __restrict__ lens,
+                   const int64_t* __restrict__ slot_off, int n_splits,
                    float scale_log2e, uint32_t* __restrict__ counters,
                    float* __restrict__ partial, float* __restrict__ O) {
     using S = Slice<E, D>;
@@ -142,9 +143,19 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
         if constexpr (!kBf16) widen<E, D>(raw, qf[g]);
     }
 
+    // Uniform batch: every (sequence, KV head) slab has kv_len rows and starts
+    // pair * head_stride in.  Ragged batch (lens != NULL): the cache is
+    // [Hkv][total_slots][D], head_stride is the plane stride, sequence b owns the
+    // slots from slot_off[b] and lens[b] of them are occupied.
+    int64_t kv_len = kv_len_uniform;
+    int64_t slab = (int64_t)pair * head_stride_bytes;
+    if (lens != nullptr) {
+        kv_len = lens[b];
+        slab = (int64_t)hkv * head_stride_bytes + slot_off[b] * (int64_t)S::kRowBytes;
+    }
     const int64_t r1 = kv_len;                   // rows at or past r1 do not exist
-    const char* Kh = Kc + (int64_t)pair * head_stride_bytes;
-    const char* Vh = Vc + (int64_t)pair * head_stride_bytes;
+    const char* Kh = Kc + slab;
+    const char* Vh = Vc + slab;
     const int lane_off = rg * S::kRowBytes + c * S::kBytes;
 
     float m[G], l[G], acc[G][EPL];    // m: running max of the RAW score (before scaling)
@@ -383,7 +394,7 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
 #pragma unroll
     for (int j = 0; j < kOut; ++j) {
         const int o = threadIdx.x + j * kDecThreads;
-        if (o < G * D) O[hq0 * D + o] = num[j] / den[j];
+        if (o < G * D) O[hq0 * D + o] = den[j] > 0.f ? num[j] / den[j] : 0.f;   // 0 for an empty cache
     }
     // leave the counter ready for the next call on this workspace
     if (threadIdx.x == 0) __hip_atomic_store(&counters[pair], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -412,9 +423,29 @@ DecodePlan decode_plan(int32_t B, int32_t Hkv, int64_t kv_len, int32_t requested
     return plan;
 }
 
+DecodePlan decode_plan_ragged(int32_t n_seq, int32_t Hkv, int64_t max_len, int32_t requested_splits) {
+    const int64_t pairs = (int64_t)n_seq * Hkv;
+    int64_t want = requested_splits;
+    if (want <= 0) {
+        // Lengths differ, so the launch relies on the hardware handing out more
+        // workgroups than fit at once: about 1024 rows of the longest sequence
+        // per workgroup, and never fewer workgroups than compute units.
+        const int64_t by_len = (max_len + 1023) / 1024;
+        const int64_t by_cu = (device_compute_units() + pairs - 1) / pairs;
+        want = by_len > by_cu ? by_len : by_cu;
+    }
+    const int64_t cap = decode_max_splits(max_len);
+    if (want > cap) want = cap;
+    if (want < 1) want = 1;
+    DecodePlan plan;
+    plan.n_splits = (int32_t)want;
+    return plan;
+}
+
 template <typename E, int D, int G>
 static l2kv_status launch_decode(const void* Q, const void* Kc, const void* Vc, int32_t B, int32_t Hq,
-                                 int32_t Hkv, int64_t kv_len, int64_t kv_head_stride, float scale,
+                                 int32_t Hkv, int64_t kv_len, int64_t kv_head_stride,
+                                 const int32_t* lens, const int64_t* slot_off, float scale,
                                  const DecodePlan& plan, float* O, void* workspace,
                                  hipStream_t stream) {
     (void)Hq;
@@ -425,7 +456,7 @@ static l2kv_status launch_decode(const void* Q, const void* Kc, const void* Vc, 
     hipLaunchKernelGGL((decode_kernel<E, D, G>), grid, dim3(kDecThreads), 0, stream,
                        static_cast<const char*>(Q), static_cast<const char*>(Kc),
                        static_cast<const char*>(Vc), (int)Hkv, kv_len,
-                       kv_head_stride * (int64_t)E::kBytes, (int)plan.n_splits,
+                       kv_head_stride * (int64_t)E::kBytes, lens, slot_off, (int)plan.n_splits,
                        scale_log2e, counters, partial, O);
     return launch_status();
 }
@@ -433,12 +464,13 @@ static l2kv_status launch_decode(const void* Q, const void* Kc, const void* Vc, 
 template <typename E, int D>
 static l2kv_status decode_by_group(int G, const void* Q, const void* Kc, const void* Vc, int32_t B,
                                    int32_t Hq, int32_t Hkv, int64_t kv_len, int64_t kv_head_stride,
-                                   float scale, const DecodePlan& plan, float* O, void* workspace,
+                                   const int32_t* lens, const int64_t* slot_off, float scale,
+                                   const DecodePlan& plan, float* O, void* workspace,
                                    hipStream_t stream) {
 #define L2KV_G(N)                                                                                   \
     case N:                                                                                         \
-        return launch_decode<E, D, N>(Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride, scale, plan, O, \
-                                      workspace, stream)
+        return launch_decode<E, D, N>(Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride, lens, slot_off, \
+                                      scale, plan, O, workspace, stream)
     switch (G) {
         L2KV_G(1); L2KV_G(2); L2KV_G(3); L2KV_G(4); L2KV_G(5); L2KV_G(6); L2KV_G(7); L2KV_G(8);
     }
@@ -448,19 +480,20 @@ static l2kv_status decode_by_group(int G, const void* Q, const void* Kc, const v
 
 l2kv_status decode_dispatch(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt, int32_t B,
                             int32_t Hq, int32_t Hkv, int64_t kv_len, int32_t D,
-                            int64_t kv_head_stride, float scale, const DecodePlan& plan, float* O,
-                            void* workspace, hipStream_t stream) {
+                            int64_t kv_head_stride, const int32_t* lens, const int64_t* slot_off,
+                            float scale, const DecodePlan& plan, float* O, void* workspace,
+                            hipStream_t stream) {
     const int G = Hq / Hkv;
     if (dt == L2KV_F32) {
         return D == 64 ? decode_by_group<F32, 64>(G, Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride,
-                                                  scale, plan, O, workspace, stream)
+                                                  lens, slot_off, scale, plan, O, workspace, stream)
                        : decode_by_group<F32, 128>(G, Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride,
-                                                   scale, plan, O, workspace, stream);
+                                                   lens, slot_off, scale, plan, O, workspace, stream);
     }
     return D == 64 ? decode_by_group<BF16, 64>(G, Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride,
-                                               scale, plan, O, workspace, stream)
+                                               lens, slot_off, scale, plan, O, workspace, stream)
                    : decode_by_group<BF16, 128>(G, Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride,
-                                                scale, plan, O, workspace, stream);
+                                                lens, slot_off, scale, plan, O, workspace, stream);
 }
 
 }  // namespace l2kv

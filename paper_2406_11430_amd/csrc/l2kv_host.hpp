@@ -42,10 +42,36 @@ inline size_t decode_counter_bytes(int32_t B, int32_t Hkv) {
     return (raw + 255) / 256 * 256;
 }
 DecodePlan decode_plan(int32_t B, int32_t Hkv, int64_t kv_len, int32_t requested_splits);
+DecodePlan decode_plan_ragged(int32_t n_seq, int32_t Hkv, int64_t max_len, int32_t requested_splits);
 
+// lens / slot_off NULL: uniform batch (kv_len rows per slab, slabs kv_head_stride apart).
+// Otherwise ragged: cache [Hkv][total_slots][D], kv_head_stride = total_slots * D,
+// kv_len = longest sequence (sizes the decomposition only).
 l2kv_status decode_dispatch(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt, int32_t B,
                             int32_t Hq, int32_t Hkv, int64_t kv_len, int32_t D,
-                            int64_t kv_head_stride, float scale, const DecodePlan& plan, float* O,
-                            void* workspace, hipStream_t stream);
+                            int64_t kv_head_stride, const int32_t* lens, const int64_t* slot_off,
+                            float scale, const DecodePlan& plan, float* O, void* workspace,
+                            hipStream_t stream);
+
+// Ragged selection / compaction and the streaming slot cache (stream.hip, select.hip).
+l2kv_status select_ragged_dispatch(const float* norms, int32_t n_planes, int32_t n_seq,
+                                   int64_t total_tokens, const int64_t* in_off, const int64_t* out_off,
+                                   int64_t total_kept, int64_t max_len, l2kv_mode mode,
+                                   int32_t* kept_idx, hipStream_t stream);
+l2kv_status compact_ragged_dispatch(const void* K, const void* V, const float* norms, l2kv_dtype dt,
+                                    const int32_t* kept_idx, int32_t n_planes, int32_t n_seq,
+                                    int64_t total_tokens, const int64_t* in_off, const int64_t* out_off,
+                                    int64_t total_kept, int64_t max_kept, const int64_t* slot_off,
+                                    int64_t total_slots, int32_t D, void* Kc, void* Vc, float* norms_c,
+                                    int32_t* pos_c, hipStream_t stream);
+l2kv_status stream_append_dispatch(const void* Knew, const void* Vnew, l2kv_dtype dt, int32_t n_layers,
+                                   int32_t n_seq, int32_t Hkv, int32_t D, const int32_t* token_ids,
+                                   const int64_t* slot_off, int64_t total_slots, const int32_t* lens_in,
+                                   int32_t* lens_out, void* Kc, void* Vc, float* norms_c, int32_t* pos_c,
+                                   hipStream_t stream);
+l2kv_status stream_evict_dispatch(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, int32_t D,
+                                  const int64_t* slot_off, int64_t total_slots, const int32_t* lens_in,
+                                  const int32_t* budgets, int32_t* lens_out, void* Kc, void* Vc,
+                                  float* norms_c, int32_t* pos_c, hipStream_t stream);
 
 }  // namespace l2kv

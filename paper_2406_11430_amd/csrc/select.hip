@@ -41,10 +41,20 @@ constexpr int kSelPackedRegs = 128;
 // E > 0 : keys of the head fit E per lane and are cached in registers.
 // E == 0: streaming variant, keys are re-read from memory (L2) in every pass.
 // E == -1: packed variant, 256 keys per lane as 16-bit halves (T <= 131072).
+// Ragged batches: [n_planes][total_in] norms, sequence s at in_off[s]..in_off[s+1];
+// its kept positions (relative to the sequence start) go to
+// [n_planes][total_out] at out_off[s]..out_off[s+1].  in_off == NULL: uniform.
+struct RaggedSelect {
+    const int64_t* in_off;
+    const int64_t* out_off;
+    int64_t n_seq, total_in, total_out;
+};
+
 template <int E>
 __global__ __launch_bounds__(E == -1 ? kSelPackedThreads : kSelThreads)
 void select_kernel(const uint32_t* __restrict__ norm_bits, int64_t T, uint32_t k, uint32_t flip,
-                   int32_t* __restrict__ kept_idx, int32_t* __restrict__ kept_count) {
+                   int32_t* __restrict__ kept_idx, int32_t* __restrict__ kept_count,
+                   RaggedSelect rag) {
     constexpr bool kInRegs = E > 0;
     constexpr bool kPacked = E == -1;
     constexpr int kWaves = (kPacked ? kSelPackedThreads : kSelThreads) / kWaveSize;
@@ -56,6 +66,19 @@ void select_kernel(const uint32_t* __restrict__ norm_bits, int64_t T, uint32_t k
     const int lane = threadIdx.x % kWaveSize;
     const int wave = threadIdx.x / kWaveSize;
     const uint32_t* src = norm_bits + head * T;
+    int32_t* out = kept_idx + head * (int64_t)k;
+    if (rag.in_off != nullptr) {
+        // ragged batch: block = (plane, sequence); sizes and places come from the offset arrays
+        const int64_t plane = head / rag.n_seq;
+        const int64_t seq = head % rag.n_seq;
+        const int64_t lo = rag.in_off[seq], olo = rag.out_off[seq];
+        T = rag.in_off[seq + 1] - lo;
+        const int64_t kk = rag.out_off[seq + 1] - olo;
+        if (T <= 0 || kk <= 0) return;                       // whole workgroup: nothing to select
+        k = (uint32_t)(kk < T ? kk : T);                     // never more than there are
+        src = norm_bits + plane * rag.total_in + lo;
+        out = kept_idx + plane * rag.total_out + olo;
+    }
 
     // Wave w owns tokens [w*span, (w+1)*span), span a multiple of 64; iteration
     // e of lane l looks at token w*span + e*64 + l.
@@ -202,7 +225,6 @@ void select_kernel(const uint32_t* __restrict__ norm_bits, int64_t T, uint32_t k
     }
     uint32_t out_base = lt_before + (eq_before < need_eq ? eq_before : need_eq);
     uint32_t eq_base = eq_before;
-    int32_t* out = kept_idx + head * (int64_t)k;
 
     auto emit = [&](uint32_t key, int64_t e) {
         const uint32_t t = t0 + (uint32_t)e * kWaveSize;
@@ -226,11 +248,30 @@ void select_kernel(const uint32_t* __restrict__ norm_bits, int64_t T, uint32_t k
 
 template <int E>
 static void launch_select(const float* norms, int64_t n_heads, int64_t T, int64_t k, uint32_t flip,
-                          int32_t* kept_idx, int32_t* kept_count, hipStream_t stream) {
+                          int32_t* kept_idx, int32_t* kept_count, hipStream_t stream,
+                          RaggedSelect rag = RaggedSelect{nullptr, nullptr, 0, 0, 0}) {
     hipLaunchKernelGGL((select_kernel<E>), dim3((unsigned)n_heads),
                        dim3(E == -1 ? kSelPackedThreads : kSelThreads), 0, stream,
                        reinterpret_cast<const uint32_t*>(norms), T, (uint32_t)k, flip, kept_idx,
-                       kept_count);
+                       kept_count, rag);
+}
+
+// Picks the kernel variant from the (longest) head length and launches it.
+static void launch_select_for_length(int64_t longest, const float* norms, int64_t n_heads, int64_t T,
+                                     int64_t k, uint32_t flip, int32_t* kept_idx, int32_t* kept_count,
+                                     hipStream_t stream, RaggedSelect rag) {
+    const int64_t per_lane = (longest + kSelThreads - 1) / kSelThreads;
+    if (per_lane <= 1)       launch_select<1>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream, rag);
+    else if (per_lane <= 2)  launch_select<2>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream, rag);
+    else if (per_lane <= 4)  launch_select<4>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream, rag);
+    else if (per_lane <= 8)  launch_select<8>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream, rag);
+    else if (per_lane <= 16) launch_select<16>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream, rag);
+    else if (per_lane <= kSelMaxRegKeys)
+        launch_select<32>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream, rag);
+    else if (longest <= (int64_t)kSelPackedThreads * 2 * kSelPackedRegs)
+        launch_select<-1>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream, rag);
+    else
+        launch_select<0>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream, rag);
 }
 
 l2kv_status select_dispatch(const float* norms, int64_t n_heads, int64_t T, int64_t k,
@@ -239,18 +280,20 @@ l2kv_status select_dispatch(const float* norms, int64_t n_heads, int64_t T, int6
     (void)workspace;
     if (n_heads > 0x7fffffffLL) return L2KV_ERR_SHAPE;
     const uint32_t flip = mode == L2KV_KEEP_HIGHEST ? 0xffffffffu : 0u;
-    const int64_t per_lane = (T + kSelThreads - 1) / kSelThreads;
-    if (per_lane <= 1)       launch_select<1>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
-    else if (per_lane <= 2)  launch_select<2>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
-    else if (per_lane <= 4)  launch_select<4>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
-    else if (per_lane <= 8)  launch_select<8>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
-    else if (per_lane <= 16) launch_select<16>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
-    else if (per_lane <= kSelMaxRegKeys)
-        launch_select<32>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
-    else if (T <= (int64_t)kSelPackedThreads * 2 * kSelPackedRegs)
-        launch_select<-1>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
-    else
-        launch_select<0>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream);
+    launch_select_for_length(T, norms, n_heads, T, k, flip, kept_idx, kept_count, stream,
+                             RaggedSelect{nullptr, nullptr, 0, 0, 0});
+    return launch_status();
+}
+
+l2kv_status select_ragged_dispatch(const float* norms, int32_t n_planes, int32_t n_seq,
+                                   int64_t total_tokens, const int64_t* in_off, const int64_t* out_off,
+                                   int64_t total_kept, int64_t max_len, l2kv_mode mode,
+                                   int32_t* kept_idx, hipStream_t stream) {
+    const int64_t blocks = (int64_t)n_planes * n_seq;
+    if (blocks > 0x7fffffffLL) return L2KV_ERR_SHAPE;
+    const uint32_t flip = mode == L2KV_KEEP_HIGHEST ? 0xffffffffu : 0u;
+    launch_select_for_length(max_len, norms, blocks, 0, 0, flip, kept_idx, nullptr, stream,
+                             RaggedSelect{in_off, out_off, n_seq, total_tokens, total_kept});
     return launch_status();
 }
 

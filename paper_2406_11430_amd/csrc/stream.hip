@@ -1,0 +1,300 @@
+// Ragged batches and the streaming slot cache.
+//
+// arXiv 2406.11430, Sec. 4 ("Language Modelling Tasks"): the cache grows up to a
+// pre-defined length, after which the tokens with the highest key norm are
+// discarded.  Here every sequence owns a fixed range of slots in each head
+// plane; a slot holds the K and V rows, the fp32 squared key norm and the
+// original token id of one kept token:
+//
+//   Kc, Vc  [n_planes][total_slots][D]      n_planes = layers x KV heads
+//   norms_c [n_planes][total_slots] fp32    pos_c [n_planes][total_slots] int32
+//   sequence s: slots slot_off[s] .. slot_off[s+1]-1, the first lens[s] occupied
+//
+// Three kernels:
+//   compact_ragged : kept rows of a ragged prompt batch -> slot cache (with norms, ids)
+//   stream_append  : one new token per sequence -> next free slot, norm computed here
+//                    (fixed summation order), so no separate norm pass is ever needed
+//   stream_evict   : while a sequence holds more than its budget, drop the slot
+//                    with the largest (norm bits, token id) and move the last
+//                    slot into the hole -- the reverse of the keep order of
+//                    l2kv_select, so the kept set is always "lowest norms, ties
+//                    to the lower token id"
+#include "l2kv_device.hpp"
+#include "l2kv_host.hpp"
+
+namespace l2kv {
+
+// ------------------------------------------------------------ compact_ragged
+constexpr int kRagThreads = 256;
+constexpr int kRagWaves = kRagThreads / kWaveSize;
+constexpr int kRagUnroll = 4;
+constexpr int kRagRowsPerBlock = kRagWaves * kRowsPerWaveLoad * kRagUnroll;   // 64
+
+// grid.x = blocks_per_seq * n_seq * n_planes (block -> (plane, seq, chunk of 64 kept rows))
+template <int W>
+__global__ __launch_bounds__(kRagThreads)
+void compact_ragged_kernel(const char* __restrict__ K, const char* __restrict__ V,
+                           const float* __restrict__ norms, const int32_t* __restrict__ kept_idx,
+                           int64_t n_seq, int64_t total_tokens, const int64_t* __restrict__ in_off,
+                           const int64_t* __restrict__ out_off, int64_t total_kept,
+                           int64_t blocks_per_seq, const int64_t* __restrict__ slot_off,
+                           int64_t total_slots, char* __restrict__ Kc, char* __restrict__ Vc,
+                           float* __restrict__ norms_c, int32_t* __restrict__ pos_c) {
+    constexpr int64_t kSliceBytes = 4 * W;
+    constexpr int64_t kRowBytes = kRowLanes * kSliceBytes;
+    const int64_t chunk = blockIdx.x % blocks_per_seq;
+    const int64_t seq = (blockIdx.x / blocks_per_seq) % n_seq;
+    const int64_t plane = blockIdx.x / (blocks_per_seq * n_seq);
+    const int lane = threadIdx.x % kWaveSize;
+    const int wave = threadIdx.x / kWaveSize;
+    const int c = lane % kRowLanes;
+    const int rg = lane / kRowLanes;
+
+    const int64_t T = in_off[seq + 1] - in_off[seq];
+    const int64_t cap = slot_off[seq + 1] - slot_off[seq];
+    int64_t k = out_off[seq + 1] - out_off[seq];
+    k = k < cap ? k : cap;                                   // never write past the sequence's slots
+    const int64_t first = chunk * kRagRowsPerBlock + (wave * kRowsPerWaveLoad + rg) * kRagUnroll;
+    if (first >= k || T <= 0) return;
+
+    const int32_t* idx = kept_idx + plane * total_kept + out_off[seq];
+    const int64_t src_seq = plane * total_tokens + in_off[seq];     // rows
+    const int64_t dst_seq = plane * total_slots + slot_off[seq];    // slots
+
+    int32_t tok[kRagUnroll];
+#pragma unroll
+    for (int u = 0; u < kRagUnroll; ++u) {
+        const int64_t j = first + u < k ? first + u : k - 1;
+        int32_t t = idx[j];
+        t = t < 0 ? 0 : (t < T ? t : (int32_t)(T - 1));      // stay inside the sequence whatever idx holds
+        tok[u] = t;
+    }
+    Words<W> kr[kRagUnroll], vr[kRagUnroll];
+#pragma unroll
+    for (int u = 0; u < kRagUnroll; ++u)
+        kr[u] = load_words_stream<W>(K + (src_seq + tok[u]) * kRowBytes + c * kSliceBytes);
+#pragma unroll
+    for (int u = 0; u < kRagUnroll; ++u)
+        vr[u] = load_words_stream<W>(V + (src_seq + tok[u]) * kRowBytes + c * kSliceBytes);
+#pragma unroll
+    for (int u = 0; u < kRagUnroll; ++u) {
+        const int64_t j = first + u;
+        if (j < k) {
+            const int64_t slot = dst_seq + j;
+            store_words<W>(Kc + slot * kRowBytes + c * kSliceBytes, kr[u]);
+            store_words<W>(Vc + slot * kRowBytes + c * kSliceBytes, vr[u]);
+            if (c == 0) {
+                norms_c[slot] = norms[src_seq + tok[u]];
+                pos_c[slot] = tok[u];
+            }
+        }
+    }
+}
+
+l2kv_status compact_ragged_dispatch(const void* K, const void* V, const float* norms, l2kv_dtype dt,
+                                    const int32_t* kept_idx, int32_t n_planes, int32_t n_seq,
+                                    int64_t total_tokens, const int64_t* in_off, const int64_t* out_off,
+                                    int64_t total_kept, int64_t max_kept, const int64_t* slot_off,
+                                    int64_t total_slots, int32_t D, void* Kc, void* Vc, float* norms_c,
+                                    int32_t* pos_c, hipStream_t stream) {
+    const int row_bytes = D * (dt == L2KV_F32 ? 4 : 2);
+    const int64_t bps = (max_kept + kRagRowsPerBlock - 1) / kRagRowsPerBlock;
+    const int64_t blocks = bps * n_seq * n_planes;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return L2KV_ERR_SHAPE;
+#define L2KV_RAG(WW)                                                                               \
+    hipLaunchKernelGGL((compact_ragged_kernel<WW>), dim3((unsigned)blocks), dim3(kRagThreads), 0,  \
+                       stream, static_cast<const char*>(K), static_cast<const char*>(V), norms,   \
+                       kept_idx, (int64_t)n_seq, total_tokens, in_off, out_off, total_kept, bps,   \
+                       slot_off, total_slots, static_cast<char*>(Kc), static_cast<char*>(Vc),      \
+                       norms_c, pos_c)
+    switch (row_bytes) {
+        case 128: L2KV_RAG(2); break;
+        case 256: L2KV_RAG(4); break;
+        case 512: L2KV_RAG(8); break;
+        default: return L2KV_ERR_SHAPE;
+    }
+#undef L2KV_RAG
+    return launch_status();
+}
+
+// -------------------------------------------------------------- stream_append
+// One 16-lane row group per (layer, sequence, KV head).  Knew, Vnew are
+// [n_layers][n_seq][Hkv][D]; the plane of (layer, head) is layer*Hkv + head.
+template <typename E, int D>
+__global__ __launch_bounds__(256)
+void stream_append_kernel(const char* __restrict__ Knew, const char* __restrict__ Vnew, int64_t n_rows,
+                          int64_t n_seq, int64_t Hkv, const int32_t* __restrict__ token_ids,
+                          const int64_t* __restrict__ slot_off, int64_t total_slots,
+                          const int32_t* __restrict__ lens_in, int32_t* __restrict__ lens_out,
+                          char* __restrict__ Kc, char* __restrict__ Vc, float* __restrict__ norms_c,
+                          int32_t* __restrict__ pos_c) {
+#pragma clang fp contract(off)
+    using S = Slice<E, D>;
+    const int c = threadIdx.x % kRowLanes;
+    int64_t r = (int64_t)blockIdx.x * (256 / kRowLanes) + threadIdx.x / kRowLanes;   // (layer, seq, head) row
+    const bool live = r < n_rows;
+    r = live ? r : n_rows - 1;                    // idle groups shadow the last row, stores skipped
+    const int64_t head = r % Hkv;
+    const int64_t seq = (r / Hkv) % n_seq;
+    const int64_t layer = r / (Hkv * n_seq);
+    const int64_t plane = layer * Hkv + head;
+
+    const int32_t len = lens_in[seq];
+    const int64_t cap = slot_off[seq + 1] - slot_off[seq];
+    const bool room = len >= 0 && len < cap;      // a full sequence is left untouched
+    const Words<S::kWords> kr = load_words<S::kWords>(Knew + r * S::kRowBytes + c * S::kBytes);
+    const Words<S::kWords> vr = load_words<S::kWords>(Vnew + r * S::kRowBytes + c * S::kBytes);
+
+    // squared norm in the library's fixed order (chunk left to right, neighbour tree)
+    float x[S::kElems];
+    widen<E, D>(kr, x);
+    float acc = x[0] * x[0];
+#pragma unroll
+    for (int e = 1; e < S::kElems; ++e) {
+        const float sq = x[e] * x[e];
+        acc = acc + sq;
+    }
+    const float norm = row16_tree_sum(acc);
+
+    if (live && room) {
+        const int64_t slot = plane * total_slots + slot_off[seq] + len;
+        store_words<S::kWords>(Kc + slot * S::kRowBytes + c * S::kBytes, kr);
+        store_words<S::kWords>(Vc + slot * S::kRowBytes + c * S::kBytes, vr);
+        if (c == 0) {
+            norms_c[slot] = norm;
+            pos_c[slot] = token_ids[seq];
+        }
+    }
+    if (live && plane == 0 && c == 0) lens_out[seq] = room ? len + 1 : len;
+}
+
+l2kv_status stream_append_dispatch(const void* Knew, const void* Vnew, l2kv_dtype dt, int32_t n_layers,
+                                   int32_t n_seq, int32_t Hkv, int32_t D, const int32_t* token_ids,
+                                   const int64_t* slot_off, int64_t total_slots, const int32_t* lens_in,
+                                   int32_t* lens_out, void* Kc, void* Vc, float* norms_c, int32_t* pos_c,
+                                   hipStream_t stream) {
+    const int64_t n_rows = (int64_t)n_layers * n_seq * Hkv;
+    const int64_t blocks = (n_rows + 15) / 16;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return L2KV_ERR_SHAPE;
+#define L2KV_APP(EE, DD)                                                                           \
+    hipLaunchKernelGGL((stream_append_kernel<EE, DD>), dim3((unsigned)blocks), dim3(256), 0, stream, \
+                       static_cast<const char*>(Knew), static_cast<const char*>(Vnew), n_rows,     \
+                       (int64_t)n_seq, (int64_t)Hkv, token_ids, slot_off, total_slots, lens_in,     \
+                       lens_out, static_cast<char*>(Kc), static_cast<char*>(Vc), norms_c, pos_c)
+    if (dt == L2KV_F32) {
+        if (D == 64) L2KV_APP(F32, 64); else L2KV_APP(F32, 128);
+    } else {
+        if (D == 64) L2KV_APP(BF16, 64); else L2KV_APP(BF16, 128);
+    }
+#undef L2KV_APP
+    return launch_status();
+}
+
+// --------------------------------------------------------------- stream_evict
+constexpr int kEvictThreads = 256;
+constexpr int kEvictWaves = kEvictThreads / kWaveSize;
+
+// One workgroup per (plane, sequence).  Every eviction is one arg-max over the
+// occupied slots of key = (norm bits << 32 | token id): per-lane scan, wave
+// reduction with shuffles, 4 wave results through LDS.  In the steady state of
+// a growing budget at most one slot goes per step.
+template <int W>
+__global__ __launch_bounds__(kEvictThreads)
+void stream_evict_kernel(int64_t n_seq, const int64_t* __restrict__ slot_off, int64_t total_slots,
+                         const int32_t* __restrict__ lens_in, const int32_t* __restrict__ budgets,
+                         int32_t* __restrict__ lens_out, char* __restrict__ Kc, char* __restrict__ Vc,
+                         float* __restrict__ norms_c, int32_t* __restrict__ pos_c) {
+    constexpr int64_t kSliceBytes = 4 * W;
+    constexpr int64_t kRowBytes = kRowLanes * kSliceBytes;
+    __shared__ unsigned long long s_key[kEvictWaves];
+    __shared__ int32_t s_slot[kEvictWaves];
+    const int64_t seq = blockIdx.x % n_seq;
+    const int64_t plane = blockIdx.x / n_seq;
+    const int lane = threadIdx.x % kWaveSize;
+    const int wave = threadIdx.x / kWaveSize;
+
+    const int64_t cap = slot_off[seq + 1] - slot_off[seq];
+    int32_t len = lens_in[seq];
+    len = len < 0 ? 0 : (len < cap ? len : (int32_t)cap);
+    int32_t budget = budgets[seq];
+    budget = budget < 0 ? 0 : budget;
+    const int64_t base = plane * total_slots + slot_off[seq];
+    const uint32_t* nb = reinterpret_cast<const uint32_t*>(norms_c) + base;
+    float* nw = norms_c + base;
+    int32_t* pw = pos_c + base;
+
+    while (len > budget) {                         // uniform over the workgroup
+        unsigned long long best = 0;
+        int32_t best_slot = -1;
+        for (int32_t j = threadIdx.x; j < len; j += kEvictThreads) {
+            const unsigned long long key = ((unsigned long long)nb[j] << 32) | (uint32_t)pw[j];
+            if (best_slot < 0 || key > best) {
+                best = key;
+                best_slot = j;
+            }
+        }
+        // keys are distinct (token ids are), so "larger key" is a total order; -1 marks "none"
+#pragma unroll
+        for (int off = kWaveSize / 2; off > 0; off >>= 1) {
+            const unsigned long long ok = __shfl_xor(best, off);
+            const int32_t os = __shfl_xor(best_slot, off);
+            if (os >= 0 && (best_slot < 0 || ok > best)) {
+                best = ok;
+                best_slot = os;
+            }
+        }
+        if (lane == 0) {
+            s_key[wave] = best;
+            s_slot[wave] = best_slot;
+        }
+        __syncthreads();
+        best = s_key[0];
+        best_slot = s_slot[0];
+#pragma unroll
+        for (int w = 1; w < kEvictWaves; ++w) {
+            if (s_slot[w] >= 0 && (best_slot < 0 || s_key[w] > best)) {
+                best = s_key[w];
+                best_slot = s_slot[w];
+            }
+        }
+        const int32_t last = len - 1;
+        if (best_slot != last) {
+            // move the last slot into the hole: first 16 lanes K, next 16 lanes V
+            if (threadIdx.x < 2 * kRowLanes) {
+                char* buf = threadIdx.x < kRowLanes ? Kc : Vc;
+                const int c = threadIdx.x % kRowLanes;
+                const Words<W> row = load_words<W>(buf + (base + last) * kRowBytes + c * kSliceBytes);
+                store_words<W>(buf + (base + best_slot) * kRowBytes + c * kSliceBytes, row);
+            } else if (threadIdx.x == 2 * kRowLanes) {
+                nw[best_slot] = nw[last];
+                pw[best_slot] = pw[last];
+            }
+        }
+        len = last;
+        __syncthreads();                            // moves visible before the next scan; LDS reusable
+    }
+    if (plane == 0 && threadIdx.x == 0) lens_out[seq] = len;
+}
+
+l2kv_status stream_evict_dispatch(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, int32_t D,
+                                  const int64_t* slot_off, int64_t total_slots, const int32_t* lens_in,
+                                  const int32_t* budgets, int32_t* lens_out, void* Kc, void* Vc,
+                                  float* norms_c, int32_t* pos_c, hipStream_t stream) {
+    const int row_bytes = D * (dt == L2KV_F32 ? 4 : 2);
+    const int64_t blocks = (int64_t)n_planes * n_seq;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return L2KV_ERR_SHAPE;
+#define L2KV_EV(WW)                                                                               \
+    hipLaunchKernelGGL((stream_evict_kernel<WW>), dim3((unsigned)blocks), dim3(kEvictThreads), 0,  \
+                       stream, (int64_t)n_seq, slot_off, total_slots, lens_in, budgets, lens_out,  \
+                       static_cast<char*>(Kc), static_cast<char*>(Vc), norms_c, pos_c)
+    switch (row_bytes) {
+        case 128: L2KV_EV(2); break;
+        case 256: L2KV_EV(4); break;
+        case 512: L2KV_EV(8); break;
+        default: return L2KV_ERR_SHAPE;
+    }
+#undef L2KV_EV
+    return launch_status();
+}
+
+}  // namespace l2kv

@@ -168,3 +168,58 @@ def test_binding_refuses_cpu_tensors():
     n = torch.zeros(1, 8)
     with pytest.raises(ValueError):
         pkg.l2kv_norms(K, n)
+
+
+def test_ragged_and_stream_validation(lib):
+    sel = lib.l2kv_select_ragged
+    assert sel(None, 8, 4, 1000, P, P, 500, 300, 0, P, None) == E_NULL
+    assert sel(P, 8, 4, 1000, None, P, 500, 300, 0, P, None) == E_NULL
+    assert sel(P, 0, 4, 1000, P, P, 500, 300, 0, P, None) == E_SHAPE
+    assert sel(P, 8, 4, 1000, P, P, 1001, 300, 0, P, None) == E_SHAPE      # kept > tokens
+    assert sel(P, 8, 4, 1000, P, P, 500, 0, 0, P, None) == E_SHAPE
+    assert sel(P, 8, 4, 1000, P, P, 500, 300, 7, P, None) == E_SHAPE       # bad mode
+    assert sel(P, 8, 4, 1000, P + 4, P, 500, 300, 0, P, None) == E_ALIGN   # int64 offsets need 8
+    cmp_ = lib.l2kv_compact_ragged
+    ok = [P, P, P, 1, P, 8, 4, 1000, P, P, 500, 200, P, 600, 128, P, P, P, P, None]
+    for i in (0, 1, 2, 4, 8, 9, 12, 15, 16, 17, 18):
+        bad = list(ok)
+        bad[i] = None
+        assert cmp_(*bad) == E_NULL, i
+    bad = list(ok); bad[3] = 9
+    assert cmp_(*bad) == E_DTYPE
+    bad = list(ok); bad[14] = 100
+    assert cmp_(*bad) == E_SHAPE
+    bad = list(ok); bad[11] = 501                                         # max_kept > total_kept
+    assert cmp_(*bad) == E_SHAPE
+    bad = list(ok); bad[15] = P + 8
+    assert cmp_(*bad) == E_ALIGN
+    app = lib.l2kv_stream_append
+    ok = [P, P, 1, 2, 4, 8, 128, P, P, 600, P, P + 64, P, P, P, P, None]
+    assert app(*[None] + ok[1:]) == E_NULL
+    bad = list(ok); bad[11] = bad[10]
+    assert app(*bad) == E_SHAPE                                           # lens_out aliases lens_in
+    bad = list(ok); bad[6] = 48
+    assert app(*bad) == E_SHAPE
+    bad = list(ok); bad[8] = P + 4
+    assert app(*bad) == E_ALIGN
+    ev = lib.l2kv_stream_evict
+    ok = [1, 16, 4, 128, P, 600, P, P, P + 64, P, P, P, P, None]
+    bad = list(ok); bad[7] = None
+    assert ev(*bad) == E_NULL
+    bad = list(ok); bad[8] = bad[6]
+    assert ev(*bad) == E_SHAPE
+    bad = list(ok); bad[0] = 5
+    assert ev(*bad) == E_DTYPE
+    dec = lib.l2kv_decode_attn_ragged
+    ws = lib.l2kv_decode_ragged_workspace_bytes(4, 8, 300, 128)
+    assert ws == lib.l2kv_decode_workspace_bytes(4, 8, 300, 128)
+    ok = [P, P, P, 1, 4, 8, 2, 128, P, P, 600, 300, 0.0, 0, P, P, ws, None]
+    assert dec(*ok[:8] + [None] + ok[9:]) == E_NULL
+    bad = list(ok); bad[11] = 601                                         # max_len > total_slots
+    assert dec(*bad) == E_SHAPE
+    bad = list(ok); bad[13] = 99
+    assert dec(*bad) == E_SHAPE
+    bad = list(ok); bad[16] = ws - 1
+    assert dec(*bad) == E_WS
+    bad = list(ok); bad[9] = P + 4
+    assert dec(*bad) == E_ALIGN

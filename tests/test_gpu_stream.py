@@ -1,0 +1,209 @@
+"""GPU parity of the ragged / streaming entry points against the CPU oracle:
+ragged selection and compaction into the slot cache, token append, ragged
+decode attention and eviction to a budget, step by step.  Token-id sets, rows,
+norm bits and lengths must match exactly; attention within 1e-4."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2406_11430_amd as l2kv
+from paper_2406_11430_amd import synth
+
+pytestmark = pytest.mark.gpu
+ATTN_BAR = 1e-4
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.fail("no HIP device visible: the gpu tests need a real MI355X")
+    l2kv.lib()
+    return torch.device("cuda:0")
+
+
+def rows(rng, shape, dt, ties=False):
+    x = rng.standard_normal(shape).astype(np.float32)
+    x *= np.exp(0.5 * rng.standard_normal(shape[:-1] + (1,))).astype(np.float32)
+    if ties:
+        x[..., ::5, :] = x[..., :1, :]
+    t = torch.from_numpy(x)
+    return t.to(torch.bfloat16) if dt == "bf16" else t
+
+
+def offsets(vals):
+    return np.concatenate([[0], np.cumsum(vals)]).astype(np.int64)
+
+
+class Batch:
+    """A ragged batch on both sides: device tensors driven through the library and
+    one oracle StreamHead per (plane, sequence)."""
+
+    def __init__(self, dev, rng, dt, D, L, Hkv, G, lens, r, steps, ties=False, budget_fn=None):
+        self.dev, self.dt, self.D, self.L, self.Hkv, self.G, self.r = dev, dt, D, L, Hkv, G, r
+        self.lens0 = list(lens)
+        self.n_seq, self.P = len(lens), L * Hkv
+        self.budget_fn = budget_fn or (lambda seen, s: oracle.keep_count(seen, r))
+        self.in_off = offsets(lens)
+        ks = [min(n, self.budget_fn(n, s)) if n > 0 else 0 for s, n in enumerate(lens)]   # prompt compressed to its budget
+        self.out_off = offsets(ks)
+        caps = [max(self.budget_fn(n + t, s) for t in range(steps + 1)) + 1 if n > 0 else 1
+                for s, n in enumerate(lens)]
+        self.slot_off = offsets(caps)
+        total, total_kept, total_slots = int(self.in_off[-1]), int(self.out_off[-1]), int(self.slot_off[-1])
+        K = rows(rng, (self.P, total, D), dt, ties)
+        V = rows(rng, (self.P, total, D), dt)
+        self.Kn, self.Vn = synth.as_numpy_bits(K), synth.as_numpy_bits(V)
+        Kd, Vd = K.to(dev), V.to(dev)
+        d_in, d_out, d_slot = (torch.from_numpy(a).to(dev) for a in (self.in_off, self.out_off, self.slot_off))
+        self.d_slot = d_slot
+
+        # ---- prompt compression on the device
+        norms = torch.empty((self.P, total), dtype=torch.float32, device=dev)
+        l2kv.l2kv_norms(Kd, norms)
+        idx = torch.full((self.P, total_kept), -1, dtype=torch.int32, device=dev)
+        l2kv.l2kv_select_ragged(norms, d_in, d_out, max(lens), idx)
+        tdt = Kd.dtype
+        self.Kc = torch.zeros((self.P, total_slots, D), dtype=tdt, device=dev)
+        self.Vc = torch.zeros_like(self.Kc)
+        self.nc = torch.zeros((self.P, total_slots), dtype=torch.float32, device=dev)
+        self.pc = torch.full((self.P, total_slots), -1, dtype=torch.int32, device=dev)
+        l2kv.l2kv_compact_ragged(Kd, Vd, norms, idx, d_in, d_out, max(ks), d_slot, self.Kc, self.Vc, self.nc, self.pc)
+        self.lensA = torch.tensor(ks, dtype=torch.int32, device=dev)
+        self.lensB = torch.zeros_like(self.lensA)
+        self.idx_host = idx.cpu().numpy()
+        self.norms_host = norms.cpu().numpy()
+
+        # ---- the same on the oracle, head by head
+        self.heads = {}
+        for p in range(self.P):
+            for s, n in enumerate(lens):
+                h = oracle.StreamHead(caps[s], D, dt)
+                if n > 0:
+                    a, b = self.in_off[s], self.in_off[s + 1]
+                    n32, _ = oracle.norms(self.Kn[p:p + 1, a:b], dt)
+                    assert np.array_equal(self.norms_host[p, a:b].view(np.uint32), n32[0].view(np.uint32))
+                    kept = oracle.select(n32, ks[s])[0]
+                    assert np.array_equal(self.idx_host[p, self.out_off[s]:self.out_off[s + 1]], kept), (p, s)
+                    h.load(self.Kn[p, a:b][kept], self.Vn[p, a:b][kept], n32[0, kept], kept.astype(np.int32))
+                self.heads[(p, s)] = h
+        self.check_cache(ks)
+
+    def check_cache(self, want_lens):
+        lens = self.lensA.cpu().numpy()
+        assert list(lens) == list(want_lens)
+        Kc, Vc = synth.as_numpy_bits(self.Kc), synth.as_numpy_bits(self.Vc)
+        nc, pc = self.nc.cpu().numpy(), self.pc.cpu().numpy()
+        for (p, s), h in self.heads.items():
+            n, a = len(h), self.slot_off[s]
+            assert n == lens[s], (p, s, n, lens[s])
+            ids, Kk, Vk, nk = h.kept()
+            order = np.argsort(pc[p, a:a + n], kind="stable")
+            assert np.array_equal(pc[p, a:a + n][order], ids), (p, s)            # same token-id set
+            assert np.array_equal(Kc[p, a:a + n][order], Kk) and np.array_equal(Vc[p, a:a + n][order], Vk)
+            assert np.array_equal(nc[p, a:a + n][order].view(np.uint32), nk.view(np.uint32))
+
+    def step(self, rng, t, n_splits=0):
+        dev, D, L, Hkv, G = self.dev, self.D, self.L, self.Hkv, self.G
+        live = [s for s, n in enumerate(self.lens0) if n > 0]
+        Kn = rows(rng, (L, self.n_seq, Hkv, D), self.dt)
+        Vn = rows(rng, (L, self.n_seq, Hkv, D), self.dt)
+        tok = torch.tensor([n + t for n in self.lens0], dtype=torch.int32, device=dev)
+        l2kv.l2kv_stream_append(Kn.to(dev), Vn.to(dev), tok, self.d_slot, self.lensA, self.lensB,
+                                self.Kc, self.Vc, self.nc, self.pc)
+        Knn, Vnn = synth.as_numpy_bits(Kn), synth.as_numpy_bits(Vn)
+        for (p, s), h in self.heads.items():
+            h.append(Knn[p // Hkv, s, p % Hkv], Vnn[p // Hkv, s, p % Hkv], self.lens0[s] + t)
+        lens_now = self.lensB.cpu().numpy()
+        assert list(lens_now) == [len(self.heads[(0, s)]) for s in range(self.n_seq)]
+
+        # ---- attention, one layer at a time
+        max_len = int(lens_now.max())
+        Hq = Hkv * G
+        ws = torch.zeros(l2kv.l2kv_decode_ragged_workspace_bytes(self.n_seq, Hq, max_len, D),
+                         dtype=torch.uint8, device=dev)
+        worst = 0.0
+        for layer in range(L):
+            Q = rows(rng, (self.n_seq, Hq, D), self.dt)
+            O = torch.full((self.n_seq, Hq, D), float("nan"), dtype=torch.float32, device=dev)
+            l2kv.l2kv_decode_attn_ragged(Q.to(dev), self.Kc[layer * Hkv:(layer + 1) * Hkv],
+                                         self.Vc[layer * Hkv:(layer + 1) * Hkv], self.lensB, self.d_slot,
+                                         max_len, O, ws, n_splits=n_splits)
+            got = O.cpu().numpy()
+            Qn = synth.as_numpy_bits(Q)
+            for s in range(self.n_seq):
+                for hk in range(Hkv):
+                    want = self.heads[(layer * Hkv + hk, s)].attend(Qn[s, hk * G:(hk + 1) * G])
+                    worst = max(worst, float(np.abs(got[s, hk * G:(hk + 1) * G] - want).max()))
+        assert worst <= ATTN_BAR, worst
+
+        # ---- evict to the budget of the tokens seen so far
+        budgets = [self.budget_fn(n + t + 1, s) for s, n in enumerate(self.lens0)]
+        l2kv.l2kv_stream_evict(self.d_slot, self.lensB, torch.tensor(budgets, dtype=torch.int32, device=dev),
+                               self.lensA, self.Kc, self.Vc, self.nc, self.pc)
+        for (p, s), h in self.heads.items():
+            h.evict_to(budgets[s])
+        self.check_cache([min(int(lens_now[s]), budgets[s]) for s in range(self.n_seq)])
+
+
+@pytest.mark.parametrize("dt,D", [("bf16", 128), ("f32", 64)])
+def test_stream_growing_budget(dev, dt, D):
+    rng = np.random.default_rng(11 + D)
+    b = Batch(dev, rng, dt, D, L=2, Hkv=2, G=2, lens=[70, 1, 333, 64, 129], r=0.5, steps=12)
+    for t in range(12):
+        b.step(rng, t)
+
+
+def test_stream_fixed_budget_with_ties_equals_one_shot_select(dev):
+    # fixed budget: the kept set after every step must be the one-shot selection over all tokens
+    # seen (the oracle pin); rows repeat so many norms tie and the token id decides
+    rng = np.random.default_rng(5)
+    lens = [40, 200, 17]
+    fixed = [24, 90, 17]
+    b = Batch(dev, rng, "bf16", 128, L=1, Hkv=3, G=4, lens=lens, r=0.5, steps=10, ties=True,
+              budget_fn=lambda seen, s: fixed[s])
+    for t in range(10):
+        b.step(rng, t, n_splits=(t % 3))
+
+
+def test_stream_budget_drop_evicts_several(dev):
+    # the budget falls by a lot in one step: the eviction loop runs many times per head
+    rng = np.random.default_rng(8)
+    lens = [100, 90]
+    after_step = [60, 60, 13, 13, 1]                 # budget after decode step t, both sequences
+
+    def budget(seen, s):
+        t = seen - lens[s] - 1                       # decode step this budget applies to
+        return after_step[t] if 0 <= t < len(after_step) else 60
+
+    b = Batch(dev, rng, "bf16", 128, L=1, Hkv=2, G=1, lens=lens, r=0.5, steps=5, budget_fn=budget)
+    for t in range(5):
+        b.step(rng, t)
+
+
+def test_ragged_decode_lengths_and_splits(dev):
+    # decode alone: lengths from 0 (zero output row) to several row tiles, every split count
+    rng = np.random.default_rng(3)
+    lens = [0, 1, 15, 64, 65, 700, 2049]
+    Hkv, G, D, dt = 2, 4, 128, "bf16"
+    slot_off = offsets([max(n, 1) + 3 for n in lens])
+    total = int(slot_off[-1])
+    K, V = rows(rng, (Hkv, total, D), dt), rows(rng, (Hkv, total, D), dt)
+    Q = rows(rng, (len(lens), Hkv * G, D), dt)
+    Kn, Vn, Qn = synth.as_numpy_bits(K), synth.as_numpy_bits(V), synth.as_numpy_bits(Q)
+    d_lens = torch.tensor(lens, dtype=torch.int32, device=dev)
+    d_off = torch.from_numpy(slot_off).to(dev)
+    smax = l2kv.l2kv_decode_max_splits(max(lens))
+    ws = torch.zeros(l2kv.l2kv_decode_ragged_workspace_bytes(len(lens), Hkv * G, max(lens), D),
+                     dtype=torch.uint8, device=dev)
+    for ns in (0, 1, 2, 5, smax):
+        O = torch.full((len(lens), Hkv * G, D), float("nan"), dtype=torch.float32, device=dev)
+        l2kv.l2kv_decode_attn_ragged(Q.to(dev), K.to(dev), V.to(dev), d_lens, d_off, max(lens), O, ws, n_splits=ns)
+        got = O.cpu().numpy()
+        assert np.all(got[0] == 0)                                   # empty sequence
+        for s, n in enumerate(lens):
+            if n == 0:
+                continue
+            a = slot_off[s]
+            want = oracle.decode_attn(Qn[s:s + 1], Kn[None, :, a:a + n], Vn[None, :, a:a + n], dt)[0]
+            assert np.abs(got[s] - want).max() <= ATTN_BAR, (ns, s)

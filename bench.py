@@ -156,13 +156,170 @@ def cpu_baseline(w: Workload, layers, dec_steps):
     }
 
 
+# ------------------------------------------------------- streaming workload (C5)
+class StreamWorkload:
+    """Ragged batch under streaming eviction: compress every prompt to keep_ratio,
+    then per decode step append the new token of every sequence (all layers, one
+    launch), attend layer by layer over the ragged slot cache, and evict down to
+    keep_count(tokens seen, keep_ratio) (all layers, one launch)."""
+
+    def __init__(self, cfg, dev):
+        self.cfg, self.dev = cfg, dev
+        L, Hkv, Hq, D, n_seq = cfg.L, cfg.Hkv, cfg.Hq, cfg.D, cfg.n_seq
+        dt = synth.torch_dtype(cfg.dtype)
+        P = L * Hkv
+        lens = synth.stream_lengths(cfg).tolist()
+        self.lens0 = lens
+        kc = l2kv.l2kv_keep_count
+        self.k0 = [kc(n, cfg.keep_ratio) for n in lens]
+        # budget after decode step t (tokens seen = prompt + t + 1) and slot capacity
+        self.budgets_host = [[kc(n + t + 1, cfg.keep_ratio) for n in lens] for t in range(cfg.decode_steps)]
+        caps = [max([self.k0[s]] + [b[s] for b in self.budgets_host]) + 1 for s in range(n_seq)]
+        off = lambda v: torch.tensor([0] + list(np.cumsum(v)), dtype=torch.int64, device=dev)   # noqa: E731
+        self.in_off, self.out_off, self.slot_off = off(lens), off(self.k0), off(caps)
+        self.total, self.total_kept, self.total_slots = sum(lens), sum(self.k0), sum(caps)
+        self.max_len, self.max_kept, self.max_cap = max(lens), max(self.k0), max(caps)
+        self.K = torch.empty((P, self.total, D), dtype=dt, device=dev)
+        self.V = torch.empty_like(self.K)
+        for layer in range(L):
+            Kl, Vl = synth.make_ragged_layer(cfg, layer, device=dev)
+            self.K[layer * Hkv:(layer + 1) * Hkv].copy_(Kl)
+            self.V[layer * Hkv:(layer + 1) * Hkv].copy_(Vl)
+            del Kl, Vl
+        self.Knew = torch.empty((cfg.decode_steps, L, n_seq, Hkv, D), dtype=dt, device=dev)
+        self.Vnew = torch.empty_like(self.Knew)
+        self.Q = torch.empty((cfg.decode_steps, L, n_seq, Hq, D), dtype=dt, device=dev)
+        for t in range(cfg.decode_steps):
+            a, b, q = synth.make_stream_step(cfg, t, device=dev)
+            self.Knew[t].copy_(a), self.Vnew[t].copy_(b), self.Q[t].copy_(q)
+        self.norms = torch.empty((P, self.total), dtype=torch.float32, device=dev)
+        self.idx = torch.empty((P, self.total_kept), dtype=torch.int32, device=dev)
+        self.Kc = torch.zeros((P, self.total_slots, D), dtype=dt, device=dev)
+        self.Vc = torch.zeros_like(self.Kc)
+        self.nc = torch.zeros((P, self.total_slots), dtype=torch.float32, device=dev)
+        self.pc = torch.zeros((P, self.total_slots), dtype=torch.int32, device=dev)
+        self.lens_init = torch.tensor(self.k0, dtype=torch.int32, device=dev)
+        self.lensA = torch.empty_like(self.lens_init)
+        self.lensB = torch.empty_like(self.lens_init)
+        self.budgets = torch.tensor(self.budgets_host, dtype=torch.int32, device=dev)
+        self.tokens = torch.tensor([[n + t for n in lens] for t in range(cfg.decode_steps)],
+                                   dtype=torch.int32, device=dev)
+        self.O = torch.empty((L, n_seq, Hq, D), dtype=torch.float32, device=dev)
+        self.ws = torch.zeros(l2kv.l2kv_decode_ragged_workspace_bytes(n_seq, Hq, self.max_cap, D),
+                              dtype=torch.uint8, device=dev)
+        self.Kc_v = [self.Kc[l * Hkv:(l + 1) * Hkv] for l in range(L)]
+        self.Vc_v = [self.Vc[l * Hkv:(l + 1) * Hkv] for l in range(L)]
+        self.Q_v = [[self.Q[t, l] for l in range(L)] for t in range(cfg.decode_steps)]
+        self.O_v = [self.O[l] for l in range(L)]
+        torch.cuda.synchronize()
+
+    def compress(self):
+        l2kv.l2kv_norms(self.K, self.norms)
+        l2kv.l2kv_select_ragged(self.norms, self.in_off, self.out_off, self.max_len, self.idx)
+        l2kv.l2kv_compact_ragged(self.K, self.V, self.norms, self.idx, self.in_off, self.out_off,
+                                 self.max_kept, self.slot_off, self.Kc, self.Vc, self.nc, self.pc)
+        self.lensA.copy_(self.lens_init)
+
+    def decode_step(self, t):
+        l2kv.l2kv_stream_append(self.Knew[t], self.Vnew[t], self.tokens[t], self.slot_off, self.lensA,
+                                self.lensB, self.Kc, self.Vc, self.nc, self.pc)
+        Qs = self.Q_v[t]
+        for layer in range(self.cfg.L):
+            l2kv.l2kv_decode_attn_ragged(Qs[layer], self.Kc_v[layer], self.Vc_v[layer], self.lensB,
+                                         self.slot_off, self.max_cap, self.O_v[layer], self.ws)
+        l2kv.l2kv_stream_evict(self.slot_off, self.lensB, self.budgets[t], self.lensA, self.Kc, self.Vc,
+                               self.nc, self.pc)
+
+    def step(self):
+        self.compress()
+        for t in range(self.cfg.decode_steps):
+            self.decode_step(t)
+
+    # algorithmic bytes
+    def compress_bytes(self):
+        cfg = self.cfg
+        P, row = cfg.L * cfg.Hkv, cfg.D * cfg.elem_bytes
+        norms = P * self.total * (row + 4)
+        select = P * (self.total * 4 + self.total_kept * 4)
+        compact = P * self.total_kept * (4 + 2 * row + 2 * row + 4 + 4 + 4)   # idx, rows in/out, norm in/out, id
+        return norms + select + compact
+
+    def decode_bytes(self):
+        """(attention bytes, append + evict bytes) summed over all decode steps."""
+        cfg = self.cfg
+        P, row = cfg.L * cfg.Hkv, cfg.D * cfg.elem_bytes
+        attn = other = 0
+        cur = list(self.k0)
+        for t in range(cfg.decode_steps):
+            after_append = [c + 1 for c in cur]
+            attn += P * sum(after_append) * 2 * row + cfg.L * cfg.n_seq * cfg.Hq * cfg.D * (cfg.elem_bytes + 4)
+            other += P * cfg.n_seq * (4 * row + 8)                               # append: rows in, rows out, norm, id
+            evicted = [max(0, a - b) for a, b in zip(after_append, self.budgets_host[t])]
+            other += P * sum(a * 8 * (1 if e else 0) + e * (4 * row + 16) for a, e in zip(after_append, evicted))
+            cur = [min(a, b) for a, b in zip(after_append, self.budgets_host[t])]
+        return attn, other
+
+
+def main_stream(args, dev):
+    cfg = synth.STREAM_CONFIGS[args.workload]
+    overridden = False
+    if args.layers:
+        cfg, overridden = cfg.scaled(L=args.layers), True
+    if args.decode_steps:
+        cfg, overridden = cfg.scaled(decode_steps=args.decode_steps), True
+    w = StreamWorkload(cfg, dev)
+    attn_bytes, other_bytes = w.decode_bytes()
+    comp_bytes = w.compress_bytes()
+    step_bytes = comp_bytes + attn_bytes + other_bytes
+    for _ in range(args.warmup):
+        w.step()
+    torch.cuda.synchronize()
+    marks = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record()
+        w.compress()
+        e[1].record()
+        for t in range(cfg.decode_steps):
+            w.decode_step(t)
+        e[2].record()
+        marks.append(e)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    comp_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in marks]))
+    dec_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in marks]))
+    value = step_bytes / (wall / args.steps) / 1e9
+    achieved = (attn_bytes + other_bytes) / dec_ms / 1e6
+    out = {
+        "metric": "compress+decode effective HBM GB/s", "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall * 1e3 / args.steps, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name + (" (size overridden)" if overridden else ""), "layers": cfg.L,
+                   "sequences": cfg.n_seq, "prompt_lengths": "uniform[%d, %d], seeded (sum %d)" % (cfg.len_lo, cfg.len_hi, w.total),
+                   "kv_heads": cfg.Hkv, "q_heads": cfg.Hq, "head_dim": cfg.D, "keep_ratio": cfg.keep_ratio,
+                   "decode_steps": cfg.decode_steps,
+                   "step": "ragged compress of all prompts + decode_steps x (append, layers x ragged attention, evict)"},
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "us_per_decode_step": round(dec_ms * 1e3 / cfg.decode_steps, 2),
+        "phases": {"compress": {"ms": round(comp_ms, 4), "GBps": round(comp_bytes / comp_ms / 1e6, 1)},
+                   "decode": {"ms": round(dec_ms, 4), "GBps": round(achieved, 1)}},
+        "roofline": {"kernel": "streaming decode step (append + ragged attention over all layers + evict)",
+                     "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "bytes_per_decode_step": (attn_bytes + other_bytes) // cfg.decode_steps},
+    }
+    print(json.dumps(out))
+
+
 # ----------------------------------------------------------------------- main
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="C3", choices=sorted(synth.CONFIGS))
+    ap.add_argument("--workload", default="C3", choices=sorted(synth.CONFIGS) + sorted(synth.STREAM_CONFIGS))
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
     ap.add_argument("--decode-steps", type=int, default=0, help="override decode steps (debug)")
     ap.add_argument("--cpu-layers", type=int, default=8)
@@ -183,6 +340,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.workload in synth.STREAM_CONFIGS:
+        return main_stream(args, dev)
     cfg = synth.CONFIGS[args.workload]
     overridden = False
     if args.layers:

@@ -33,6 +33,7 @@ import torch
 
 __all__ = [
     "CacheConfig", "CONFIGS", "layer_seed", "make_layer", "make_query",
+    "StreamConfig", "STREAM_CONFIGS", "stream_lengths", "make_ragged_layer", "make_stream_step",
     "span_start", "ragged_lengths", "torch_dtype", "as_numpy_bits",
 ]
 
@@ -84,6 +85,88 @@ CONFIGS: Dict[str, CacheConfig] = {
                       T=131072, dtype="bf16", keep_ratio=0.1, decode_steps=16,
                       span_len=64, span_scale=0.3),
 }
+
+
+@dataclass(frozen=True)
+class StreamConfig:
+    """Ragged streaming batch: sequences of different prompt lengths, compressed to
+    keep_ratio, then decoded step by step with the ratio enforced incrementally."""
+    name: str
+    config_id: int
+    L: int
+    n_seq: int
+    len_lo: int
+    len_hi: int
+    Hkv: int
+    Hq: int
+    D: int
+    dtype: str
+    keep_ratio: float
+    decode_steps: int
+    sink_tokens: int = 4
+    sink_scale: float = 0.1
+
+    @property
+    def G(self) -> int:
+        return self.Hq // self.Hkv
+
+    @property
+    def elem_bytes(self) -> int:
+        return 4 if self.dtype == "f32" else 2
+
+    def scaled(self, **kw) -> "StreamConfig":
+        return replace(self, **kw)
+
+
+STREAM_CONFIGS: Dict[str, StreamConfig] = {
+    # Batched streaming decode: 64 sequences, prompt lengths uniform in [1024, 8192].
+    "C5": StreamConfig("C5-streaming-ragged", 5, L=32, n_seq=64, len_lo=1024, len_hi=8192, Hkv=8, Hq=32,
+                       D=128, dtype="bf16", keep_ratio=0.5, decode_steps=256),
+}
+
+
+def stream_lengths(cfg: StreamConfig) -> torch.Tensor:
+    """Prompt lengths of the batch (int64, CPU), seeded."""
+    return ragged_lengths(cfg.n_seq, cfg.len_lo, cfg.len_hi, 424242 + cfg.config_id)
+
+
+def _scaled_rows(shape, g, dev, dt, sink_rows=None, sink_scale=1.0):
+    x = torch.randn(shape, generator=g, device=dev, dtype=torch.float32)
+    z = torch.randn(shape[:-1] + (1,), generator=g, device=dev, dtype=torch.float32)
+    s = torch.exp(0.5 * z)
+    if sink_rows is not None:
+        s[..., sink_rows, :] *= sink_scale
+    return (x * s).to(dt)
+
+
+def make_ragged_layer(cfg: StreamConfig, layer: int, device="cpu") -> Tuple[torch.Tensor, torch.Tensor]:
+    """Prompt K and V of one layer, ``[Hkv][total_tokens][D]``: the sequences of the
+    batch back to back in every head plane; the first tokens of every sequence
+    are low-norm sinks."""
+    dev = torch.device(device)
+    g = torch.Generator(device=dev)
+    g.manual_seed(1234 + 1000 * cfg.config_id + layer)
+    dt = torch_dtype(cfg.dtype)
+    lens = stream_lengths(cfg)
+    total = int(lens.sum())
+    starts = torch.cumsum(lens, 0) - lens
+    sink = torch.cat([torch.arange(int(a), int(a) + min(cfg.sink_tokens, int(n))) for a, n in zip(starts, lens)]).to(dev)
+    K = _scaled_rows((cfg.Hkv, total, cfg.D), g, dev, dt, sink, cfg.sink_scale)
+    V = torch.randn((cfg.Hkv, total, cfg.D), generator=g, device=dev, dtype=torch.float32).to(dt)
+    return K, V
+
+
+def make_stream_step(cfg: StreamConfig, step: int, device="cpu"):
+    """New tokens and queries of one decode step: Knew, Vnew ``[L][n_seq][Hkv][D]``,
+    Q ``[L][n_seq][Hq][D]``."""
+    dev = torch.device(device)
+    g = torch.Generator(device=dev)
+    g.manual_seed((1234 + 1000 * cfg.config_id) * 7919 + step)
+    dt = torch_dtype(cfg.dtype)
+    Knew = _scaled_rows((cfg.L, cfg.n_seq, cfg.Hkv, cfg.D), g, dev, dt)
+    Vnew = torch.randn((cfg.L, cfg.n_seq, cfg.Hkv, cfg.D), generator=g, device=dev, dtype=torch.float32).to(dt)
+    Q = torch.randn((cfg.L, cfg.n_seq, cfg.Hq, cfg.D), generator=g, device=dev, dtype=torch.float32).to(dt)
+    return Knew, Vnew, Q
 
 
 def torch_dtype(name: str) -> torch.dtype:

@@ -118,3 +118,66 @@ def test_c4_retrieval_shape_131k(dev):
         assert in_span_got > cfg.span_len // 2          # most of the planted span survives 90 % eviction
     del w
     torch.cuda.empty_cache()
+
+
+def test_c5_streaming_batch_sampled_heads(dev):
+    # the ragged streaming batch at its real per-launch shapes (64 sequences, prompt lengths
+    # 1024..8192, 8 KV / 32 Q heads), 4 of its 32 layers and 24 of its 256 decode steps; the
+    # oracle replays sampled (plane, sequence) heads token by token
+    import bench
+    cfg = synth.STREAM_CONFIGS["C5"].scaled(L=4, decode_steps=24)
+    w = bench.StreamWorkload(cfg, dev)
+    w.compress()
+    lens = w.lens0
+    rng = np.random.default_rng(55)
+    longest, shortest = int(np.argmax(lens)), int(np.argmin(lens))
+    samples = {(0, longest), (cfg.L * cfg.Hkv - 1, shortest)}
+    while len(samples) < 6:
+        samples.add((int(rng.integers(cfg.L * cfg.Hkv)), int(rng.integers(cfg.n_seq))))
+    samples = sorted(samples)
+    in_off, out_off, slot_off = (t.cpu().numpy() for t in (w.in_off, w.out_off, w.slot_off))
+    caps = np.diff(slot_off)
+    heads = {}
+    for (p, s) in samples:
+        a, b = in_off[s], in_off[s + 1]
+        Kn, Vn = synth.as_numpy_bits(w.K[p, a:b]), synth.as_numpy_bits(w.V[p, a:b])
+        n32, _ = oracle.norms(Kn[None], cfg.dtype)
+        kept = oracle.select(n32, w.k0[s])[0]
+        assert np.array_equal(w.idx[p, out_off[s]:out_off[s + 1]].cpu().numpy(), kept)
+        assert kept[0] == 0                                    # the first sink token survives
+        h = oracle.StreamHead(int(caps[s]), cfg.D, cfg.dtype)
+        h.load(Kn[kept], Vn[kept], n32[0, kept], kept.astype(np.int32))
+        heads[(p, s)] = h
+
+    def check_slots(lens_dev):
+        for (p, s), h in heads.items():
+            n, a = len(h), slot_off[s]
+            assert int(lens_dev[s]) == n
+            ids, Kk, Vk, nk = h.kept()
+            pc = w.pc[p, a:a + n].cpu().numpy()
+            order = np.argsort(pc, kind="stable")
+            assert np.array_equal(pc[order], ids)
+            assert np.array_equal(synth.as_numpy_bits(w.Kc[p, a:a + n])[order], Kk)
+            assert np.array_equal(synth.as_numpy_bits(w.Vc[p, a:a + n])[order], Vk)
+            assert np.array_equal(w.nc[p, a:a + n].cpu().numpy()[order].view(np.uint32), nk.view(np.uint32))
+
+    check_slots(w.lensA.cpu().numpy())
+    G, worst = cfg.G, 0.0
+    for t in range(cfg.decode_steps):
+        w.decode_step(t)
+        torch.cuda.synchronize()
+        O = w.O.cpu().numpy()
+        for (p, s), h in heads.items():
+            layer, hk = p // cfg.Hkv, p % cfg.Hkv
+            h.append(synth.as_numpy_bits(w.Knew[t, layer, s, hk]), synth.as_numpy_bits(w.Vnew[t, layer, s, hk]),
+                     lens[s] + t)
+            want = h.attend(synth.as_numpy_bits(w.Q[t, layer, s, hk * G:(hk + 1) * G]))
+            worst = max(worst, float(np.abs(O[layer, s, hk * G:(hk + 1) * G] - want).max()))
+            h.evict_to(w.budgets_host[t][s])
+        if t % 6 == 5 or t == cfg.decode_steps - 1:
+            check_slots(w.lensA.cpu().numpy())
+    assert worst <= 2e-3 and worst <= 1e-4, worst
+    # every sequence ends at its budget, in every plane the same count
+    assert w.lensA.cpu().tolist() == w.budgets_host[cfg.decode_steps - 1]
+    del w
+    torch.cuda.empty_cache()

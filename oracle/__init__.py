@@ -72,6 +72,8 @@ def _load():
         lib.l2kv_oracle_decode_attn.argtypes = [
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_int, c.c_int32, c.c_int32,
             c.c_int32, c.c_int64, c.c_int32, c.c_int64, c.c_double, c.c_void_p]
+        lib.l2kv_oracle_random_keys.restype = None
+        lib.l2kv_oracle_random_keys.argtypes = [c.c_int64, c.c_int64, c.c_uint32, c.c_void_p]
         lib.l2kv_oracle_stream_append.restype = c.c_int
         lib.l2kv_oracle_stream_append.argtypes = [
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int,
@@ -172,6 +174,14 @@ def compress(K: np.ndarray, V: np.ndarray, dtype, keep_ratio: float,
         k = keep_count(K.shape[-2], keep_ratio)
     idx = select(n32, k, mode)
     return n32, n64, idx, compact(K, idx), compact(V, idx)
+
+
+def random_keys(n_heads: int, T: int, seed: int) -> np.ndarray:
+    """Keys of the keep-random control (Sec. 4): ``[n_heads, T]`` float32 whose BIT
+    PATTERNS are a counter-based hash of (seed, head, token); feed to ``select``."""
+    keys = np.empty((n_heads, T), dtype=np.float32)
+    _load().l2kv_oracle_random_keys(int(n_heads), int(T), int(seed) & 0xFFFFFFFF, keys.ctypes.data)
+    return keys
 
 
 class StreamHead:

@@ -328,3 +328,27 @@ int l2kv_oracle_stream_evict(void *K, void *V, float *norms, int32_t *pos, int32
     }
     return evicted;
 }
+
+/* ------------------------------------------------------------------------
+ * Keep-random control (Sec. 4: "keeping random tokens").  The random order is
+ * a counter-based hash of (seed, head, token) so that it can be reproduced
+ * anywhere: x = token*0x9E3779B1 + head*0x85EBCA77 + seed (mod 2^32), followed
+ * by the 32-bit finalizer of MurmurHash3 (x ^= x>>16; x *= 0x85EBCA6B;
+ * x ^= x>>13; x *= 0xC2B2AE35; x ^= x>>16).  The keys are written as bit
+ * patterns into an fp32 array; selection orders by bit pattern, so
+ * l2kv_oracle_select on them keeps the k tokens with the lowest hash.
+ * ------------------------------------------------------------------------ */
+void l2kv_oracle_random_keys(int64_t n_heads, int64_t T, uint32_t seed, float *keys)
+{
+    for (int64_t h = 0; h < n_heads; ++h) {
+        for (int64_t t = 0; t < T; ++t) {
+            uint32_t x = (uint32_t)t * 0x9E3779B1u + (uint32_t)h * 0x85EBCA77u + seed;
+            x ^= x >> 16;
+            x *= 0x85EBCA6Bu;
+            x ^= x >> 13;
+            x *= 0xC2B2AE35u;
+            x ^= x >> 16;
+            memcpy(&keys[h * T + t], &x, sizeof x);
+        }
+    }
+}

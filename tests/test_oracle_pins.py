@@ -488,3 +488,30 @@ def test_stream_growing_budget_and_attention():
         assert len(head) == oracle.keep_count(tok + 1, r)
         # evicting is monotone: a token once dropped never comes back, the newest may be dropped at once
         assert set(head.kept()[0]) <= set(ids)
+
+
+# ------------------------------------------------------------ keep-random control
+def test_random_keys_hash_known_values_and_spread():
+    # hand-evaluated values of the stated hash (token*0x9E3779B1 + head*0x85EBCA77 + seed, then the
+    # MurmurHash3 32-bit finalizer), computed here with Python integers
+    def ref(seed, h, t):
+        x = (t * 0x9E3779B1 + h * 0x85EBCA77 + seed) & 0xFFFFFFFF
+        x ^= x >> 16
+        x = (x * 0x85EBCA6B) & 0xFFFFFFFF
+        x ^= x >> 13
+        x = (x * 0xC2B2AE35) & 0xFFFFFFFF
+        x ^= x >> 16
+        return x
+    keys = oracle.random_keys(3, 50, 12345).view(np.uint32)
+    for h in range(3):
+        for t in (0, 1, 7, 49):
+            assert int(keys[h, t]) == ref(12345, h, t)
+    assert ref(0, 0, 0) == 0                               # the finalizer maps 0 to 0
+    # a bijection of the counter: distinct inside a head, different between heads and seeds
+    big = oracle.random_keys(2, 4096, 7).view(np.uint32)
+    assert len(np.unique(big[0])) == 4096 and not np.array_equal(big[0], big[1])
+    assert not np.array_equal(oracle.random_keys(1, 64, 1), oracle.random_keys(1, 64, 2))
+    # the kept set is spread evenly over the sequence (each quarter holds about a quarter)
+    kept = oracle.select(oracle.random_keys(1, 4096, 99), 2048)[0]
+    counts = np.histogram(kept, bins=4, range=(0, 4096))[0]
+    assert counts.sum() == 2048 and counts.min() > 430 and counts.max() < 600

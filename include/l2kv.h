@@ -109,6 +109,17 @@ l2kv_status l2kv_select_k(const float* norms, int64_t n_heads, int64_t T,
 size_t l2kv_select_workspace_bytes(int64_t n_heads, int64_t T);
 
 /*
+ * Keys for the keep-random control of Sec. 4 ("keeping random tokens"):
+ * keys[i][t] receives, as a 32-bit pattern stored in an fp32 array, the hash
+ *     x = t*0x9E3779B1 + i*0x85EBCA77 + seed   (mod 2^32)
+ *     x ^= x>>16; x *= 0x85EBCA6B; x ^= x>>13; x *= 0xC2B2AE35; x ^= x>>16
+ * (the 32-bit finalizer of MurmurHash3).  l2kv_select_k orders by bit pattern,
+ * so running it on these keys instead of norms keeps k pseudo-random tokens per
+ * head, reproducibly.  keys out: [n_heads][T].  Errors: NULL, SHAPE, ALIGN, LAUNCH.
+ */
+l2kv_status l2kv_random_keys(int64_t n_heads, int64_t T, uint32_t seed, float* keys, void* stream);
+
+/*
  * Compaction ("...and the corresponding values", Sec. 1): the kept rows of K
  * and of V copied, byte for byte and in the order of kept_idx, into dense
  * caches:

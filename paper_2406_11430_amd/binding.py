@@ -30,6 +30,7 @@ SIGNATURES = {
     "l2kv_select_k": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_void_p,
                                 C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "l2kv_select_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64]),
+    "l2kv_random_keys": (C.c_int, [C.c_int64, C.c_int64, C.c_uint32, C.c_void_p, C.c_void_p]),
     "l2kv_compact": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int64, C.c_int64,
                                C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]),
     "l2kv_decode_attn": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32,
@@ -183,6 +184,15 @@ def l2kv_select_k(norms: torch.Tensor, k: int, mode: int, kept_idx: torch.Tensor
                                                 _ptr(kept_count), _ptr(workspace),
                                                 workspace.numel() * workspace.element_size(),
                                                 _stream(stream)))
+
+
+def l2kv_random_keys(seed: int, keys: torch.Tensor, stream=None) -> None:
+    """keys ``[..., T]`` float32 (pre-allocated) <- hash bit patterns of (seed, head, token)."""
+    _dev(keys)
+    T = keys.shape[-1]
+    assert keys.dtype == torch.float32
+    _check("l2kv_random_keys", lib().l2kv_random_keys(keys.numel() // T, T, int(seed) & 0xFFFFFFFF,
+                                                      _ptr(keys), _stream(stream)))
 
 
 def l2kv_compact(K: torch.Tensor, V: Optional[torch.Tensor], kept_idx: torch.Tensor,

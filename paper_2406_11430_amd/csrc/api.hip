@@ -160,6 +160,14 @@ l2kv_status l2kv_decode_attn(const void* Q, const void* Kc, const void* Vc, l2kv
                                    workspace, workspace_bytes, stream);
 }
 
+l2kv_status l2kv_random_keys(int64_t n_heads, int64_t T, uint32_t seed, float* keys, void* stream) {
+    if (keys == nullptr) return L2KV_ERR_NULL;
+    if (n_heads <= 0 || n_heads > kMaxHeads || T <= 0 || T > kMaxTokens) return L2KV_ERR_SHAPE;
+    if (n_heads > (int64_t{1} << 62) / T) return L2KV_ERR_SHAPE;
+    if (!aligned(keys, 4)) return L2KV_ERR_ALIGN;
+    return random_keys_dispatch(n_heads, T, seed, keys, static_cast<hipStream_t>(stream));
+}
+
 /* ---- ragged batches and the streaming slot cache ------------------------- */
 
 l2kv_status l2kv_select_ragged(const float* norms, int32_t n_planes, int32_t n_seq,

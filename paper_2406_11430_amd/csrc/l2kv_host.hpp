@@ -23,6 +23,8 @@ l2kv_status select_dispatch(const float* norms, int64_t n_heads, int64_t T, int6
                             l2kv_mode mode, int32_t* kept_idx, int32_t* kept_count,
                             void* workspace, hipStream_t stream);
 
+l2kv_status random_keys_dispatch(int64_t n_heads, int64_t T, uint32_t seed, float* keys, hipStream_t stream);
+
 l2kv_status compact_dispatch(const void* K, const void* V, l2kv_dtype dt, const int32_t* kept_idx,
                              int64_t n_heads, int64_t T, int64_t k, int32_t D, int64_t head_stride,
                              void* Kc, void* Vc, hipStream_t stream);

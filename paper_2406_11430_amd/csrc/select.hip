@@ -274,6 +274,34 @@ static void launch_select_for_length(int64_t longest, const float* norms, int64_
         launch_select<0>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream, rag);
 }
 
+// Keys of the keep-random control (arXiv 2406.11430 Sec. 4, "keeping random
+// tokens"): a counter-based hash of (seed, head, token) written as bit patterns
+// into an fp32 array, on which l2kv_select_k then keeps the k lowest.  The hash
+// is x = token*0x9E3779B1 + head*0x85EBCA77 + seed followed by the 32-bit
+// finalizer of MurmurHash3.
+__global__ __launch_bounds__(256)
+void random_keys_kernel(int64_t total, int64_t T, uint32_t seed, uint32_t* __restrict__ keys) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const uint32_t head = (uint32_t)(i / T), t = (uint32_t)(i % T);
+    uint32_t x = t * 0x9E3779B1u + head * 0x85EBCA77u + seed;
+    x ^= x >> 16;
+    x *= 0x85EBCA6Bu;
+    x ^= x >> 13;
+    x *= 0xC2B2AE35u;
+    x ^= x >> 16;
+    keys[i] = x;
+}
+
+l2kv_status random_keys_dispatch(int64_t n_heads, int64_t T, uint32_t seed, float* keys, hipStream_t stream) {
+    const int64_t total = n_heads * T;
+    const int64_t blocks = (total + 255) / 256;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return L2KV_ERR_SHAPE;
+    hipLaunchKernelGGL(random_keys_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, total, T, seed,
+                       reinterpret_cast<uint32_t*>(keys));
+    return launch_status();
+}
+
 l2kv_status select_dispatch(const float* norms, int64_t n_heads, int64_t T, int64_t k,
                             l2kv_mode mode, int32_t* kept_idx, int32_t* kept_count,
                             void* workspace, hipStream_t stream) {

@@ -349,3 +349,59 @@ def test_kept_set_ignores_values_on_gpu(dev):
         Kp = K[:, :, perm].contiguous()
         c, _ = gpu_select(gpu_norms(Kp.to(dev)), k)
         assert set(perm[c[0, 0].cpu()].tolist()) == set(a[0, 0].cpu().tolist())
+
+
+# ------------------------------------------------- control strategies of Sec. 4
+def test_keep_random_control_matches_oracle(dev):
+    n_heads, T, k, seed = 6, 3000, 1000, 20240611
+    keys = torch.empty((n_heads, T), dtype=torch.float32, device=dev)
+    l2kv.l2kv_random_keys(seed, keys)
+    want_keys = oracle.random_keys(n_heads, T, seed)
+    assert np.array_equal(keys.cpu().numpy().view(np.uint32), want_keys.view(np.uint32))
+    idx, _ = gpu_select(keys, k)
+    assert np.array_equal(idx.cpu().numpy(), oracle.select(want_keys, k))
+
+
+def test_keep_highest_control_is_complement_of_lowest(dev):
+    rng = np.random.default_rng(21)
+    T, k = 4096, 1024
+    n = np.exp(rng.standard_normal((3, T))).astype(np.float32)
+    nd = torch.from_numpy(n).to(dev)
+    hi, _ = gpu_select(nd, k, l2kv.L2KV_KEEP_HIGHEST)
+    lo, _ = gpu_select(nd, T - k, l2kv.L2KV_KEEP_LOWEST)
+    for h in range(3):
+        a, b = set(hi[h].cpu().tolist()), set(lo[h].cpu().tolist())
+        assert not (a & b) and len(a | b) == T
+    assert np.array_equal(hi.cpu().numpy(), oracle.select(n, k, oracle.MODE_HIGHEST))
+
+
+def test_per_head_keep_counts_through_the_ragged_entry_points(dev):
+    # per-head compression ratios (the paper's Sec. 8 outlook) and per-layer skipping (Sec. 4: the
+    # first layers are left uncompressed) are the ragged calls with one plane and one
+    # "sequence" per head: k_i = T keeps a head whole
+    rng = np.random.default_rng(31)
+    n_heads, T, D = 5, 700, 128
+    ks = [700, 350, 1, 123, 699]                                 # head 0 is "skipped" (kept whole)
+    K = rand_cache(rng, (1, n_heads * T, D), "bf16")
+    V = rand_cache(rng, (1, n_heads * T, D), "bf16")
+    Kd, Vd = to_dev(K, "bf16", dev), to_dev(V, "bf16", dev)
+    in_off = torch.arange(n_heads + 1, dtype=torch.int64, device=dev) * T
+    out_off = torch.tensor([0] + list(np.cumsum(ks)), dtype=torch.int64, device=dev)
+    norms = gpu_norms(Kd)
+    idx = torch.empty((1, sum(ks)), dtype=torch.int32, device=dev)
+    l2kv.l2kv_select_ragged(norms, in_off, out_off, T, idx)
+    Kc = torch.zeros((1, sum(ks), D), dtype=torch.bfloat16, device=dev)
+    Vc = torch.zeros_like(Kc)
+    nc = torch.zeros((1, sum(ks)), dtype=torch.float32, device=dev)
+    pc = torch.zeros((1, sum(ks)), dtype=torch.int32, device=dev)
+    l2kv.l2kv_compact_ragged(Kd, Vd, norms, idx, in_off, out_off, max(ks), out_off, Kc, Vc, nc, pc)
+    n32, _ = oracle.norms(K[0].reshape(n_heads, T, D), "bf16")
+    o = 0
+    for h, k in enumerate(ks):
+        want = oracle.select(n32[h:h + 1], k)[0]
+        assert np.array_equal(idx[0, o:o + k].cpu().numpy(), want)
+        assert np.array_equal(pc[0, o:o + k].cpu().numpy(), want)
+        assert np.array_equal(synth.as_numpy_bits(Kc[0, o:o + k]), K[0, h * T:(h + 1) * T][want])
+        assert np.array_equal(synth.as_numpy_bits(Vc[0, o:o + k]), V[0, h * T:(h + 1) * T][want])
+        o += k
+    assert np.array_equal(idx[0, :T].cpu().numpy(), np.arange(T))   # the skipped head is untouched

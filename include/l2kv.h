@@ -181,6 +181,13 @@ l2kv_status l2kv_decode_attn_splits(const void* Q, const void* Kc, const void* V
                                     void* stream);
 
 int32_t l2kv_decode_max_splits(int64_t kv_len);
+
+/* Zero-fills a decode workspace with a small kernel on `stream` (the "zero
+ * before first use" of l2kv_decode_attn; safe under graph capture, where a
+ * memset node is not).  workspace_bytes: the size from
+ * l2kv_decode_workspace_bytes (always a multiple of 16).
+ * Errors: NULL, WORKSPACE (size 0 or not a multiple of 16), ALIGN, LAUNCH. */
+l2kv_status l2kv_decode_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 size_t  l2kv_decode_workspace_bytes(int32_t B, int32_t Hq, int64_t kv_len, int32_t D);
 
 /* ------------------------------------------------------------------------

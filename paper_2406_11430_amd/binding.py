@@ -41,6 +41,7 @@ SIGNATURES = {
                                           C.c_float, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
                                           C.c_void_p]),
     "l2kv_decode_max_splits": (C.c_int32, [C.c_int64]),
+    "l2kv_decode_workspace_init": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p]),
     "l2kv_decode_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int64, C.c_int32]),
     "l2kv_select_ragged": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_int64, C.c_int, C.c_void_p, C.c_void_p]),
@@ -136,6 +137,13 @@ def l2kv_decode_workspace_bytes(B: int, Hq: int, kv_len: int, D: int) -> int:
 
 def l2kv_decode_max_splits(kv_len: int) -> int:
     return int(lib().l2kv_decode_max_splits(int(kv_len)))
+
+
+def l2kv_decode_workspace_init(workspace: torch.Tensor, stream=None) -> None:
+    """Zero-fill a decode workspace on the stream (required once before first use)."""
+    _dev(workspace)
+    _check("l2kv_decode_workspace_init", lib().l2kv_decode_workspace_init(
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def l2kv_version() -> int:

@@ -119,12 +119,21 @@ l2kv_status l2kv_compact(const void* K, const void* V, l2kv_dtype dt, const int3
 
 int32_t l2kv_decode_max_splits(int64_t kv_len) { return decode_max_splits(kv_len); }
 
+l2kv_status l2kv_decode_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+    if (workspace == nullptr) return L2KV_ERR_NULL;
+    if (workspace_bytes < 16 || workspace_bytes % 16 != 0) return L2KV_ERR_WORKSPACE;
+    if (!aligned(workspace, 16)) return L2KV_ERR_ALIGN;
+    return workspace_init_dispatch(workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
 size_t l2kv_decode_workspace_bytes(int32_t B, int32_t Hq, int64_t kv_len, int32_t D) {
     if (B <= 0 || Hq <= 0 || kv_len <= 0 || D <= 0) return 0;
     // counters (at most one per query head: Hkv <= Hq) + split partials
-    return decode_counter_bytes(B, Hq) +
-           static_cast<size_t>(B) * static_cast<size_t>(Hq) *
-               static_cast<size_t>(decode_max_splits(kv_len)) * static_cast<size_t>(D + 2) * sizeof(float);
+    const size_t raw = decode_counter_bytes(B, Hq) +
+                       static_cast<size_t>(B) * static_cast<size_t>(Hq) *
+                           static_cast<size_t>(decode_max_splits(kv_len)) * static_cast<size_t>(D + 2) *
+                           sizeof(float);
+    return (raw + 255) / 256 * 256;
 }
 
 l2kv_status l2kv_decode_attn_splits(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt,

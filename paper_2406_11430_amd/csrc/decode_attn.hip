@@ -400,6 +400,23 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
     if (threadIdx.x == 0) __hip_atomic_store(&counters[pair], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Zero-fill of a decode workspace as a kernel (callers under graph capture
+// cannot record a memset node reliably; a fill kernel is always safe).
+__global__ __launch_bounds__(256)
+void workspace_fill_kernel(uint4* __restrict__ p, size_t n_vec) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n_vec) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+l2kv_status workspace_init_dispatch(void* workspace, size_t bytes, hipStream_t stream) {
+    const size_t n_vec = bytes / 16;
+    const size_t blocks = (n_vec + 255) / 256;
+    if (blocks == 0 || blocks > 0x7fffffffULL) return L2KV_ERR_SHAPE;
+    hipLaunchKernelGGL(workspace_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       static_cast<uint4*>(workspace), n_vec);
+    return launch_status();
+}
+
 int32_t decode_max_splits(int64_t kv_len) {
     if (kv_len <= 0) return 0;
     const int64_t by_rows = (kv_len + kDecodeRowTile - 1) / kDecodeRowTile;

@@ -125,7 +125,7 @@ def test_compact_validation(lib):
 def test_decode_validation(lib):
     f = lib.l2kv_decode_attn
     ws = lib.l2kv_decode_workspace_bytes(2, 8, 100, 128)
-    assert ws == 256 + 2 * 8 * lib.l2kv_decode_max_splits(100) * 130 * 4   # counters + partials
+    assert ws == (256 + 2 * 8 * lib.l2kv_decode_max_splits(100) * 130 * 4 + 255) // 256 * 256   # counters + partials, padded
     a = (P, P, P, 1, 2, 8, 2, 100, 128, 12800, 0.0, P, P, ws, None)
 
     def call(**kw):
@@ -150,6 +150,19 @@ def test_decode_validation(lib):
     g = lib.l2kv_decode_attn_splits
     assert g(P, P, P, 1, 2, 8, 2, 100, 128, 12800, 0.0, 3, P, P, ws, None) == E_SHAPE   # > max splits (2)
     assert g(P, P, P, 1, 2, 8, 2, 100, 128, 12800, 0.0, -1, P, P, ws, None) == E_SHAPE
+
+
+def test_workspace_init_and_random_keys_validation(lib):
+    f = lib.l2kv_decode_workspace_init
+    assert f(None, 256, None) == E_NULL
+    assert f(P, 0, None) == E_WS and f(P, 100, None) == E_WS      # not a multiple of 16
+    assert f(P + 8, 256, None) == E_ALIGN
+    g = lib.l2kv_random_keys
+    assert g(4, 100, 1, None, None) == E_NULL
+    assert g(0, 100, 1, P, None) == E_SHAPE and g(4, 0, 1, P, None) == E_SHAPE
+    assert g(4, 100, 1, P + 2, None) == E_ALIGN
+    for B, Hq, n, D in ((1, 1, 1, 64), (4, 32, 16384, 128), (3, 7, 1000, 128)):
+        assert lib.l2kv_decode_workspace_bytes(B, Hq, n, D) % 16 == 0
 
 
 def test_decode_max_splits(lib):

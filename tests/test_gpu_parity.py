@@ -250,6 +250,21 @@ def test_decode_closed_forms_on_gpu(dev):
     assert np.abs(c.cpu().numpy() - oracle.decode_attn(Q, K, V, dt, scale=0.3)).max() <= ATTN_BAR
 
 
+def test_decode_workspace_init_entry_point(dev):
+    # a workspace full of garbage, cleared by the library's own fill kernel, then reused
+    rng = np.random.default_rng(44)
+    B, Hq, Hkv, n, D, dt = 2, 8, 2, 900, 128, "bf16"
+    Q, K, V = attn_case(rng, B, Hq, Hkv, n, D, dt)
+    Qd, Kd, Vd = to_dev(Q, dt, dev), to_dev(K, dt, dev), to_dev(V, dt, dev)
+    ws = torch.full((l2kv.l2kv_decode_workspace_bytes(B, Hq, n, D),), 0xAB, dtype=torch.uint8, device=dev)
+    l2kv.l2kv_decode_workspace_init(ws)
+    want = oracle.decode_attn(Q, K, V, dt)
+    for _ in range(3):                              # the counters return to zero after every call
+        O = torch.full((B, Hq, D), float("nan"), dtype=torch.float32, device=dev)
+        l2kv.l2kv_decode_attn(Qd, Kd, Vd, O, ws)
+        assert np.abs(O.cpu().numpy() - want).max() <= ATTN_BAR
+
+
 def test_decode_large_logits_are_stable(dev):
     # keys aligned with the query at a large scale: softmax saturates on one row
     B, Hq, Hkv, n, D = 1, 4, 1, 500, 128

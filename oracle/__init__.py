@@ -15,6 +15,11 @@ Functions, each following the passage named in the C source:
 * ``compress(K, V, dtype, r)``    -- the three compression steps in sequence
 * ``StreamHead``                  -- one (sequence, head) cache under streaming
                                      eviction (Sec. 4, language-modelling setting)
+* ``attn_probs(Q, K, dtype)``     -- attention scores a_p of one query over the full cache (Eq. 2)
+* ``drop_order(n32)``             -- positions in the order the norm rule discards them
+* ``attention_loss(a, n32, m)``   -- attention mass of the m dropped pairs (Eq. 5)
+* ``attention_loss_ref(a, m)``    -- the same for the ideal rule (lowest attention first)
+* ``alr(a, n32)``                 -- gap Y^m (Eq. 6) for m = 1..T and its sum Y (Eq. 7)
 """
 from __future__ import annotations
 
@@ -235,3 +240,86 @@ class StreamHead:
         n = len(self)
         order = np.argsort(self.pos[:n], kind="stable")
         return self.pos[:n][order], self.K[:n][order], self.V[:n][order], self.norms[:n][order]
+
+
+# ---------------------------------------------------------------------------
+# Attention-loss analysis (Sec. 3, Eq. 5-7).  NumPy, float64.
+# ---------------------------------------------------------------------------
+
+def _to_f64(x: np.ndarray, dtype) -> np.ndarray:
+    x = _check(x, dtype)
+    if _DT[dtype] == BF16:                       # bf16 = upper half of an fp32 bit pattern
+        return (x.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return x.astype(np.float64)
+
+
+def attn_probs(Q: np.ndarray, K: np.ndarray, dtype, scale: float = 0.0) -> np.ndarray:
+    """Attention scores of one query per head over ALL cached keys (Eq. 2):
+    Q ``[B, Hq, D]``, K ``[B, Hkv, T, D]`` -> a ``[B, Hq, T]`` float64, each row a
+    softmax of q.K_p / sqrt(D) (or q.K_p * scale when scale > 0).  Query head hq
+    reads KV head hq // (Hq // Hkv)."""
+    q, k = _to_f64(Q, dtype), _to_f64(K, dtype)
+    B, Hq, D = q.shape
+    Bk, Hkv, T, Dk = k.shape
+    assert (Bk, Dk) == (B, D) and Hq % Hkv == 0
+    G = Hq // Hkv
+    a = np.empty((B, Hq, T), dtype=np.float64)
+    for b in range(B):
+        for hq in range(Hq):
+            s = k[b, hq // G] @ q[b, hq]
+            s = s * scale if scale > 0.0 else s / np.sqrt(float(D))
+            e = np.exp(s - s.max())
+            a[b, hq] = e / e.sum()
+    return a
+
+
+def drop_order(n32: np.ndarray) -> np.ndarray:
+    """For one head, n32 ``[T]`` float32 -> the T positions in the order the
+    norm rule discards them: highest squared norm first; among equal norms the
+    later token goes first (the selection keeps the earlier one, Sec. 1 rule as
+    read by ``select``).  The m dropped pairs D of Eq. 5 are the first m entries."""
+    n32 = np.ascontiguousarray(n32, dtype=np.float32)
+    assert n32.ndim == 1
+    bits = n32.view(np.uint32)
+    keep_order = np.lexsort((np.arange(n32.shape[0]), bits))      # ascending (bits, index)
+    return keep_order[::-1].copy()
+
+
+def attention_loss(a: np.ndarray, n32: np.ndarray, m: int) -> float:
+    """Eq. 5 for the norm rule: sum of the attention scores of the m dropped pairs."""
+    D = drop_order(n32)[:m]
+    return float(np.sum(np.asarray(a, dtype=np.float64)[D]))
+
+
+def attention_loss_ref(a: np.ndarray, m: int) -> float:
+    """Reference loss of Eq. 6: the ideal rule drops the m lowest attention scores."""
+    return float(np.sum(np.sort(np.asarray(a, dtype=np.float64))[:m]))
+
+
+def alr(a: np.ndarray, n32: np.ndarray) -> Tuple[float, np.ndarray]:
+    """For one head, a ``[T]`` attention scores and n32 ``[T]`` squared norms ->
+    (Y, Ym) with Ym[m-1] = L^m - L^{m,ref} for m = 1..T (Eq. 6) and Y their sum
+    (Eq. 7)."""
+    a = np.asarray(a, dtype=np.float64)
+    T = a.shape[0]
+    L = np.cumsum(a[drop_order(n32)])             # L[m-1]     = loss of dropping m pairs by norm
+    Lref = np.cumsum(np.sort(a))                  # Lref[m-1]  = loss of dropping the m lowest scores
+    Ym = L - Lref
+    assert Ym.shape == (T,)
+    return float(Ym.sum()), Ym
+
+
+def alr_heads(Q: np.ndarray, K: np.ndarray, n32: np.ndarray, dtype, m: int, scale: float = 0.0):
+    """Per query head: (Y, L^m, L^{m,ref}), each ``[B, Hq]`` float64, from raw Q
+    ``[B, Hq, D]``, K ``[B, Hkv, T, D]`` and the squared norms n32 ``[B, Hkv, T]``."""
+    a = attn_probs(Q, K, dtype, scale)
+    B, Hq, T = a.shape
+    G = Hq // K.shape[1]
+    Y = np.empty((B, Hq)); Lm = np.empty((B, Hq)); Lref = np.empty((B, Hq))
+    for b in range(B):
+        for hq in range(Hq):
+            nh = n32[b, hq // G]
+            Y[b, hq] = alr(a[b, hq], nh)[0]
+            Lm[b, hq] = attention_loss(a[b, hq], nh, m)
+            Lref[b, hq] = attention_loss_ref(a[b, hq], m)
+    return Y, Lm, Lref

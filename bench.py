@@ -313,6 +313,66 @@ def main_stream(args, dev):
     print(json.dumps(out))
 
 
+def main_alr(args, dev):
+    """Attention-loss analysis (Sec. 3, Eq. 5-7) at the shape of one layer of the
+    chosen workload, repeated over `--layers` layers (default 4): discard ranks
+    from the key norms, then losses and Y for one query per head."""
+    cfg = synth.CONFIGS[args.workload]
+    L = args.layers or 4
+    B, Hkv, Hq, T, D = cfg.B, cfg.Hkv, cfg.Hq, cfg.T, cfg.D
+    k = l2kv.l2kv_keep_count(T, cfg.keep_ratio)
+    layers = [synth.make_layer(cfg, l, dev) for l in range(L)]
+    queries = [synth.make_query(cfg, l, 0, dev) for l in range(L)]
+    norms = torch.empty((B, Hkv, T), dtype=torch.float32, device=dev)
+    rank = torch.empty((B, Hkv, T), dtype=torch.int32, device=dev)
+    ws_r = torch.empty(l2kv.l2kv_norm_ranks_workspace_bytes(B * Hkv, T), dtype=torch.uint8, device=dev)
+    ws_a = torch.empty(l2kv.l2kv_alr_workspace_bytes(B, Hq, T), dtype=torch.uint8, device=dev)
+    out = [torch.empty((L, B, Hq), dtype=torch.float64, device=dev) for _ in range(3)]
+
+    def one_pass(marks=None):
+        for l in range(L):
+            K = layers[l][0]
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if marks is not None else None
+            if e: e[0].record()
+            l2kv.l2kv_norms(K, norms)
+            if e: e[1].record()
+            l2kv.l2kv_norm_ranks(norms, rank, ws_r)
+            if e: e[2].record()
+            l2kv.l2kv_alr(queries[l], K, rank, T - k, out[0][l], out[1][l], out[2][l], ws_a)
+            if e:
+                e[3].record()
+                marks.append(e)
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize()
+    marks = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_pass(marks)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in marks]).mean(axis=0)
+    row = D * cfg.elem_bytes
+    n = B * Hkv
+    alr_bytes = n * T * row + 2 * B * Hq * T * 4 + n * T * 4      # K once, logits out and back in, ranks in
+    Y, Lm, Lref = (o.cpu().numpy() for o in out)
+    res = {
+        "metric": "attention-loss analysis, query heads per second", "unit": "heads/s",
+        "value": round(L * B * Hq * args.steps / wall, 1), "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(wall * 1e3 / args.steps, 3), "higher_is_better": True,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name + " (attention-loss analysis, %d layers)" % L, "batch": B, "kv_heads": Hkv,
+                   "q_heads": Hq, "head_dim": D, "cached_tokens": T, "dropped_pairs_m": T - k},
+        "ms_per_layer": {"norms": round(float(ms[0]), 4), "norm_ranks": round(float(ms[1]), 4),
+                         "alr": round(float(ms[2]), 4)},
+        "alr_GBps": round(alr_bytes / ms[2] / 1e6, 1),
+        "results": {"mean_Y_over_T": round(float(Y.mean()) / T, 6), "mean_loss": round(float(Lm.mean()), 6),
+                    "mean_loss_ref": round(float(Lref.mean()), 6)},
+    }
+    print(json.dumps(res))
+
+
 # ----------------------------------------------------------------------- main
 def main():
     ap = argparse.ArgumentParser()
@@ -325,6 +385,9 @@ def main():
     ap.add_argument("--cpu-layers", type=int, default=8)
     ap.add_argument("--cpu-decode-steps", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--alr", action="store_true",
+                    help="time the attention-loss analysis (norm ranks + losses + Y) at the workload's "
+                         "per-layer shape instead of the hot path")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (torch) before the timed region: "
                          "the known-size kernel that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -342,6 +405,8 @@ def main():
 
     if args.workload in synth.STREAM_CONFIGS:
         return main_stream(args, dev)
+    if args.alr:
+        return main_alr(args, dev)
     cfg = synth.CONFIGS[args.workload]
     overridden = False
     if args.layers:

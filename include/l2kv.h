@@ -296,6 +296,63 @@ l2kv_status l2kv_decode_attn_ragged(const void* Q, const void* Kc, const void* V
 
 size_t l2kv_decode_ragged_workspace_bytes(int32_t n_seq, int32_t Hq, int64_t max_len, int32_t D);
 
+/* ---------------------------------------------------------------------------
+ * Attention-loss analysis (Sec. 3, Eq. 5-7)
+ *
+ * When m of the T cached pairs of a head are dropped, the attention loss L^m is
+ * the sum of the attention scores a_p (softmax of Eq. 2 over the FULL cache) of
+ * the dropped pairs (Eq. 5).  The norm rule drops the highest key norms; the
+ * ideal rule, which would need the next query in advance, drops the lowest
+ * scores and gives the reference loss L^{m,ref}.  Y^m = L^m - L^{m,ref} >= 0
+ * (Eq. 6) and Y = sum over m = 1..T of Y^m (Eq. 7) measure how far the norm
+ * order is from the ideal order for that head and query.
+ * ------------------------------------------------------------------------ */
+
+/*
+ * Discard order of the norm rule.  drop_rank[h][t] = number of positions of
+ * head h that are discarded before position t when pairs go highest norm
+ * first and, among equal norms, later position first -- the exact reverse of
+ * the keep order of l2kv_select, so l2kv_select(k) keeps the positions with
+ * drop_rank >= T-k and the m dropped pairs of Eq. 5 are those with
+ * drop_rank < m.  Each row of drop_rank is a permutation of 0..T-1.
+ *   norms     in : [n_heads][T] fp32, dense (as written by l2kv_norms)
+ *   drop_rank out: [n_heads][T] int32
+ *   workspace    : l2kv_norm_ranks_workspace_bytes(n_heads, T) bytes of device
+ *                  memory, 16-byte aligned; contents irrelevant before and after
+ * n_heads <= 2^31-1, T <= 2^31-1.  Errors: NULL, SHAPE, WORKSPACE, ALIGN, LAUNCH.
+ */
+l2kv_status l2kv_norm_ranks(const float* norms, int64_t n_heads, int64_t T, int32_t* drop_rank,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+size_t l2kv_norm_ranks_workspace_bytes(int64_t n_heads, int64_t T);
+
+/*
+ * Attention loss of one query per head over the uncompressed cache:
+ *   a[b][hq][p]      = softmax_p( scale * Q[b][hq] . K[b][hq / (Hq/Hkv)][p] )       (Eq. 2)
+ *   loss[b][hq]      = L^m      = sum of a_p over drop_rank[b][hkv][p] < m          (Eq. 5)
+ *   loss_ref[b][hq]  = L^{m,ref} = sum of the m smallest a_p                        (Eq. 6)
+ *   alr[b][hq]       = Y = sum_{m'=1..T} ( L^{m'} - L^{m',ref} )                    (Eq. 7)
+ *   Q         in : [B][Hq][D], dense, dtype dt
+ *   K         in : [B][Hkv] slabs of [T][D], k_head_stride elements apart, dtype dt
+ *   drop_rank in : [B][Hkv][T] int32 from l2kv_norm_ranks (values outside 0..T-1
+ *                  are not detected and give meaningless sums)
+ *   m            : number of dropped pairs for loss / loss_ref, 0..T
+ *                  (T - k for a cache compressed to k rows)
+ *   scale        : softmax scale; <= 0 selects 1/sqrt(D)
+ *   alr, loss, loss_ref out: [B][Hq] double each; loss and loss_ref may be NULL
+ *   workspace    : l2kv_alr_workspace_bytes(B, Hq, T) bytes, 16-byte aligned;
+ *                  contents irrelevant before and after
+ * Scores are computed in fp32 and summed in fp64; Hq/Hkv <= 8, B*Hkv <= 65535.
+ * All device pointers; enqueues on `stream` and returns.
+ * Errors: NULL, DTYPE, SHAPE, WORKSPACE, ALIGN, LAUNCH.
+ */
+l2kv_status l2kv_alr(const void* Q, const void* K, l2kv_dtype dt, const int32_t* drop_rank, int32_t B,
+                     int32_t Hq, int32_t Hkv, int64_t T, int32_t D, int64_t k_head_stride, float scale,
+                     int64_t m, double* alr, double* loss, double* loss_ref, void* workspace,
+                     size_t workspace_bytes, void* stream);
+
+size_t l2kv_alr_workspace_bytes(int32_t B, int32_t Hq, int64_t T);
+
 /* Static, NUL-terminated description of a status code. */
 const char* l2kv_status_string(l2kv_status s);
 

@@ -60,6 +60,13 @@ SIGNATURES = {
                                           C.c_float, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
                                           C.c_void_p]),
     "l2kv_decode_ragged_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int64, C.c_int32]),
+    "l2kv_norm_ranks": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t,
+                                  C.c_void_p]),
+    "l2kv_norm_ranks_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64]),
+    "l2kv_alr": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                           C.c_int64, C.c_int32, C.c_int64, C.c_float, C.c_int64, C.c_void_p, C.c_void_p,
+                           C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "l2kv_alr_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int64]),
     "l2kv_status_string": (C.c_char_p, [C.c_int]),
     "l2kv_version": (C.c_int32, []),
 }
@@ -335,4 +342,43 @@ def l2kv_decode_attn_ragged(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor,
     _check("l2kv_decode_attn_ragged", lib().l2kv_decode_attn_ragged(
         _ptr(Q), _ptr(Kc), _ptr(Vc), _dtype_code(Q), n_seq, Hq, Hkv, D, _ptr(lens), _ptr(slot_offsets),
         total_slots, int(max_len), float(scale), int(n_splits), _ptr(O), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+# ------------------------------------------------------------ attention-loss analysis
+def l2kv_norm_ranks_workspace_bytes(n_heads: int, T: int) -> int:
+    return int(lib().l2kv_norm_ranks_workspace_bytes(int(n_heads), int(T)))
+
+
+def l2kv_alr_workspace_bytes(B: int, Hq: int, T: int) -> int:
+    return int(lib().l2kv_alr_workspace_bytes(int(B), int(Hq), int(T)))
+
+
+def l2kv_norm_ranks(norms: torch.Tensor, drop_rank: torch.Tensor, workspace: torch.Tensor,
+                    stream=None) -> None:
+    """norms ``[..., T]`` float32 -> drop_rank ``[..., T]`` int32 (pre-allocated)."""
+    _dev(norms, drop_rank, workspace)
+    T = norms.shape[-1]
+    n = norms.numel() // T
+    assert norms.dtype == torch.float32 and drop_rank.dtype == torch.int32 and drop_rank.numel() == n * T
+    _check("l2kv_norm_ranks", lib().l2kv_norm_ranks(
+        _ptr(norms), n, T, _ptr(drop_rank), _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _stream(stream)))
+
+
+def l2kv_alr(Q: torch.Tensor, K: torch.Tensor, drop_rank: torch.Tensor, m: int, alr: torch.Tensor,
+             loss: Optional[torch.Tensor], loss_ref: Optional[torch.Tensor], workspace: torch.Tensor,
+             scale: float = 0.0, stream=None) -> None:
+    """Q ``[B, Hq, D]``, K ``[B, Hkv, T, D]``, drop_rank ``[B, Hkv, T]`` int32 -> alr, loss,
+    loss_ref ``[B, Hq]`` float64 (pre-allocated; the last two optional)."""
+    _dev(Q, K, drop_rank, alr, loss, loss_ref, workspace)
+    B, Hq, D = Q.shape
+    Bk, Hkv, T, Dk = K.shape
+    assert (Bk, Dk) == (B, D) and K.dtype == Q.dtype
+    assert drop_rank.dtype == torch.int32 and drop_rank.numel() == B * Hkv * T
+    for out in (alr, loss, loss_ref):
+        assert out is None or (out.dtype == torch.float64 and out.numel() == B * Hq)
+    _check("l2kv_alr", lib().l2kv_alr(
+        _ptr(Q), _ptr(K), _dtype_code(Q), _ptr(drop_rank), B, Hq, Hkv, T, D, T * D, float(scale), int(m),
+        _ptr(alr), _ptr(loss), _ptr(loss_ref), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)))

@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libl2kv.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "norms.hip", "select.hip", "compact.hip", "decode_attn.hip", "stream.hip"]
+SOURCES = ["api.hip", "norms.hip", "select.hip", "compact.hip", "decode_attn.hip", "stream.hip", "alr.hip"]
 ARCH = "gfx950"
 
 # -packed-fp32-ops is switched off on purpose: the compiler must not form

@@ -290,6 +290,50 @@ l2kv_status l2kv_decode_attn_ragged(const void* Q, const void* Kc, const void* V
                            lens, slot_offsets, s, plan, O, workspace, static_cast<hipStream_t>(stream));
 }
 
+/* ---- attention-loss analysis ---------------------------------------------- */
+
+size_t l2kv_norm_ranks_workspace_bytes(int64_t n_heads, int64_t T) {
+    if (n_heads <= 0 || n_heads > kMaxHeads || T <= 0 || T > kMaxTokens) return 0;
+    return norm_ranks_workspace_bytes(n_heads, T);
+}
+
+l2kv_status l2kv_norm_ranks(const float* norms, int64_t n_heads, int64_t T, int32_t* drop_rank,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    if (norms == nullptr || drop_rank == nullptr) return L2KV_ERR_NULL;
+    if (n_heads <= 0 || n_heads > kMaxHeads || T <= 0 || T > kMaxTokens) return L2KV_ERR_SHAPE;
+    if (n_heads > (int64_t{1} << 58) / T) return L2KV_ERR_SHAPE;
+    if (workspace == nullptr || workspace_bytes < norm_ranks_workspace_bytes(n_heads, T))
+        return L2KV_ERR_WORKSPACE;
+    if (!aligned(norms, 4) || !aligned(drop_rank, 4) || !aligned(workspace, 16)) return L2KV_ERR_ALIGN;
+    return norm_ranks_dispatch(norms, n_heads, T, drop_rank, workspace, static_cast<hipStream_t>(stream));
+}
+
+size_t l2kv_alr_workspace_bytes(int32_t B, int32_t Hq, int64_t T) {
+    if (B <= 0 || Hq <= 0 || T <= 0 || T > kMaxTokens) return 0;
+    return alr_workspace_bytes(B, Hq, T);
+}
+
+l2kv_status l2kv_alr(const void* Q, const void* K, l2kv_dtype dt, const int32_t* drop_rank, int32_t B,
+                     int32_t Hq, int32_t Hkv, int64_t T, int32_t D, int64_t k_head_stride, float scale,
+                     int64_t m, double* alr, double* loss, double* loss_ref, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+    if (Q == nullptr || K == nullptr || drop_rank == nullptr || alr == nullptr) return L2KV_ERR_NULL;
+    if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || T <= 0 || T > kMaxTokens || !dim_ok(D)) return L2KV_ERR_SHAPE;
+    if (Hq % Hkv != 0 || Hq / Hkv > 8) return L2KV_ERR_SHAPE;
+    if (static_cast<int64_t>(B) * Hkv > 65535 || static_cast<int64_t>(B) * Hq > 0x7fffffffLL)
+        return L2KV_ERR_SHAPE;
+    if (k_head_stride < T * static_cast<int64_t>(D)) return L2KV_ERR_SHAPE;
+    if (m < 0 || m > T || !std::isfinite(scale)) return L2KV_ERR_SHAPE;
+    if (workspace == nullptr || workspace_bytes < alr_workspace_bytes(B, Hq, T)) return L2KV_ERR_WORKSPACE;
+    if ((k_head_stride * elem_bytes(dt)) % 16 != 0) return L2KV_ERR_ALIGN;
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(drop_rank, 4) || !aligned(alr, 8) ||
+        !aligned(loss, 8) || !aligned(loss_ref, 8) || !aligned(workspace, 16))
+        return L2KV_ERR_ALIGN;
+    return alr_dispatch(Q, K, dt, drop_rank, B, Hq, Hkv, T, D, k_head_stride, scale, m, alr, loss, loss_ref,
+                        workspace, static_cast<hipStream_t>(stream));
+}
+
 const char* l2kv_status_string(l2kv_status s) {
     switch (s) {
         case L2KV_OK: return "ok";

@@ -77,4 +77,14 @@ l2kv_status stream_evict_dispatch(l2kv_dtype dt, int32_t n_planes, int32_t n_seq
                                   const int32_t* budgets, int32_t* lens_out, void* Kc, void* Vc,
                                   float* norms_c, int32_t* pos_c, hipStream_t stream);
 
+// Attention-loss analysis (alr.hip).
+size_t norm_ranks_workspace_bytes(int64_t n_heads, int64_t T);
+size_t alr_workspace_bytes(int32_t B, int32_t Hq, int64_t T);
+l2kv_status norm_ranks_dispatch(const float* norms, int64_t n_heads, int64_t T, int32_t* drop_rank,
+                                void* workspace, hipStream_t stream);
+l2kv_status alr_dispatch(const void* Q, const void* K, l2kv_dtype dt, const int32_t* drop_rank, int32_t B,
+                         int32_t Hq, int32_t Hkv, int64_t T, int32_t D, int64_t k_head_stride, float scale,
+                         int64_t m, double* alr, double* loss, double* loss_ref, void* workspace,
+                         hipStream_t stream);
+
 }  // namespace l2kv

@@ -236,3 +236,39 @@ def test_ragged_and_stream_validation(lib):
     assert dec(*bad) == E_WS
     bad = list(ok); bad[9] = P + 4
     assert dec(*bad) == E_ALIGN
+
+
+def test_attention_loss_validation(lib):
+    wr = lib.l2kv_norm_ranks_workspace_bytes(3, 1000)
+    assert wr == (3 * 1000 * 16 + 255) // 256 * 256 and lib.l2kv_norm_ranks_workspace_bytes(0, 5) == 0
+    f = lib.l2kv_norm_ranks
+    assert f(None, 3, 1000, P, P, wr, None) == E_NULL and f(P, 3, 1000, None, P, wr, None) == E_NULL
+    assert f(P, 0, 1000, P, P, wr, None) == E_SHAPE and f(P, 3, 0, P, P, wr, None) == E_SHAPE
+    assert f(P, 3, 2 ** 31, P, P, wr, None) == E_SHAPE
+    assert f(P, 3, 1000, P, None, wr, None) == E_WS and f(P, 3, 1000, P, P, wr - 1, None) == E_WS
+    assert f(P + 2, 3, 1000, P, P, wr, None) == E_ALIGN and f(P, 3, 1000, P, P + 8, wr, None) == E_ALIGN
+
+    wa = lib.l2kv_alr_workspace_bytes(2, 8, 100)
+    assert wa == (2 * 8 * 100 * 8 + 255) // 256 * 256 and lib.l2kv_alr_workspace_bytes(2, 8, 0) == 0
+    g = lib.l2kv_alr
+    a = (P, P, 1, P, 2, 8, 2, 100, 128, 12800, 0.0, 50, P, P, P, P, wa, None)
+    names = ["Q", "K", "dt", "rank", "B", "Hq", "Hkv", "T", "D", "stride", "scale", "m", "alr", "loss",
+             "loss_ref", "ws", "ws_bytes", "stream"]
+
+    def call(**kw):
+        args = list(a)
+        for key, val in kw.items():
+            args[names.index(key)] = val
+        return g(*args)
+
+    for key in ("Q", "K", "rank", "alr"):
+        assert call(**{key: None}) == E_NULL
+    assert call(dt=5) == E_DTYPE
+    assert call(B=0) == E_SHAPE and call(T=0) == E_SHAPE and call(D=96) == E_SHAPE
+    assert call(Hq=7) == E_SHAPE and call(Hq=18) == E_SHAPE
+    assert call(stride=100 * 128 - 1) == E_SHAPE
+    assert call(m=-1) == E_SHAPE and call(m=101) == E_SHAPE
+    assert call(scale=float("inf")) == E_SHAPE
+    assert call(ws=None) == E_WS and call(ws_bytes=wa - 1) == E_WS
+    assert call(Q=P + 4) == E_ALIGN and call(alr=P + 4) == E_ALIGN and call(loss=P + 4) == E_ALIGN
+    assert call(ws=P + 8) == E_ALIGN

@@ -50,6 +50,10 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
 template <int W>
 __device__ __forceinline__ Words<W> stream_words(const char* p) { return load_words_stream<W>(p); }
 
+// s_waitcnt immediate for "vmcnt(0)" alone on gfx9-family encodings: vmcnt in bits
+// [3:0] and [15:14] = 0, expcnt [6:4] and lgkmcnt [11:8] left at their maxima.
+constexpr int kWaitVmcnt0 = 0x0F70;
+
 // Device-scope (agent) relaxed store / load of one float.
 __device__ __forceinline__ void publish(float* p, float v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -105,7 +109,7 @@ __global__ __launch_bounds__(kDecThreads)
 void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
                    const char* __restrict__ Vc, int Hkv, int64_t kv_len_uniform,
                    int64_t head_stride_bytes, const int32_t* __restrict__ lens,
-                   const int64_t* __restrict__ slot_off, int n_splits,
+                   const int64_t* __restrict__ slot_off, int n_splits_grid, int rows_per_wg,
                    float scale_log2e, uint32_t* __restrict__ counters,
                    float* __restrict__ partial, float* __restrict__ O) {
     using S = Slice<E, D>;
@@ -131,6 +135,30 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
     const int rg = lane / kRowLanes;
     const int64_t hq0 = (int64_t)b * Hq + (int64_t)hkv * G;   // first query head of the group
 
+    // Uniform batch: every (sequence, KV head) slab has kv_len rows and starts
+    // pair * head_stride in.  Ragged batch (lens != NULL): the cache is
+    // [Hkv][total_slots][D], head_stride is the plane stride, sequence b owns the
+    // slots slot_off[b] .. slot_off[b+1]-1 and lens[b] of them are occupied
+    // (offsets and length are clamped into the plane, so inconsistent arrays
+    // cannot lead outside the cache).  A sequence only employs as many of the
+    // launched workgroups as it has blocks of rows_per_wg rows; the others
+    // leave at once.
+    int64_t kv_len = kv_len_uniform;
+    int64_t slab = (int64_t)pair * head_stride_bytes;
+    int n_splits = n_splits_grid;
+    if (lens != nullptr) {
+        const int64_t total_slots = head_stride_bytes / S::kRowBytes;
+        int64_t first = slot_off[b], end = slot_off[b + 1];
+        first = first < 0 ? 0 : (first > total_slots ? total_slots : first);
+        end = end < first ? first : (end > total_slots ? total_slots : end);
+        kv_len = lens[b];
+        kv_len = kv_len < 0 ? 0 : (kv_len > end - first ? end - first : kv_len);
+        slab = (int64_t)hkv * head_stride_bytes + first * (int64_t)S::kRowBytes;
+        const int64_t need = (kv_len + rows_per_wg - 1) / rows_per_wg;
+        n_splits = need < 1 ? 1 : (need < n_splits_grid ? (int)need : n_splits_grid);
+        if (split >= n_splits) return;
+    }
+
     // This lane's slice of the G query rows: raw bf16 pairs for the packed dot,
     // fp32 values otherwise.  The scale is applied to the reduced score.
     uint32_t qw[G][W];
@@ -143,16 +171,6 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
         if constexpr (!kBf16) widen<E, D>(raw, qf[g]);
     }
 
-    // Uniform batch: every (sequence, KV head) slab has kv_len rows and starts
-    // pair * head_stride in.  Ragged batch (lens != NULL): the cache is
-    // [Hkv][total_slots][D], head_stride is the plane stride, sequence b owns the
-    // slots from slot_off[b] and lens[b] of them are occupied.
-    int64_t kv_len = kv_len_uniform;
-    int64_t slab = (int64_t)pair * head_stride_bytes;
-    if (lens != nullptr) {
-        kv_len = lens[b];
-        slab = (int64_t)hkv * head_stride_bytes + slot_off[b] * (int64_t)S::kRowBytes;
-    }
     const int64_t r1 = kv_len;                   // rows at or past r1 do not exist
     const char* Kh = Kc + slab;
     const char* Vh = Vc + slab;
@@ -320,7 +338,7 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
         // Device-scope stores: written through to the level every compute unit
         // of the device reads from, so the merging workgroup below sees them
         // without any bulk cache write-back.
-        float* out = partial + ((hq0 + g) * n_splits + split) * (D + 2);
+        float* out = partial + ((hq0 + g) * n_splits_grid + split) * (D + 2);
         publish(out + d, num);
         if (d == 0) {
             publish(out + D, mx);
@@ -330,10 +348,15 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
 
     // ---- the last workgroup of this KV head merges all row ranges ---------
     // Hand-over protocol: every partial is written with a device-scope store;
-    // the barrier waits until this workgroup's stores have completed; one lane
-    // then takes a ticket with a device-scope atomic.  The workgroup that draws
-    // the last ticket re-reads all partials with device-scope loads.  No lane
-    // ever waits on another workgroup, so nothing here can hang.
+    // every wave then waits until its own stores have been acknowledged
+    // (vmcnt(0): a workgroup barrier alone does not wait for outstanding global
+    // stores, and the ticket below travels to a different memory channel than
+    // the partials, so without the wait it could overtake them); after the
+    // barrier one lane takes a ticket with a device-scope atomic.  The
+    // workgroup that draws the last ticket re-reads all partials with
+    // device-scope loads.  No lane ever waits on another workgroup, so nothing
+    // here can hang.
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
     __syncthreads();
     if (threadIdx.x == 0)
         s_ticket = __hip_atomic_fetch_add(&counters[pair], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -363,7 +386,7 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
 #pragma unroll
             for (int i = 0; i < kMergeBatch; ++i) {
                 const int sp = s0 + i < n_splits ? s0 + i : n_splits - 1;   // clamp: in bounds, ignored below
-                const float* p = partial + ((hq0 + g) * n_splits + sp) * (D + 2);
+                const float* p = partial + ((hq0 + g) * n_splits_grid + sp) * (D + 2);
                 v[j][i] = fetch(p + d);
                 pm[j][i] = fetch(p + D);
                 pl[j][i] = fetch(p + D + 1);
@@ -437,25 +460,34 @@ DecodePlan decode_plan(int32_t B, int32_t Hkv, int64_t kv_len, int32_t requested
     if (want < 1) want = 1;
     DecodePlan plan;
     plan.n_splits = (int32_t)want;
+    plan.rows_per_wg = 1;
     return plan;
 }
 
 DecodePlan decode_plan_ragged(int32_t n_seq, int32_t Hkv, int64_t max_len, int32_t requested_splits) {
     const int64_t pairs = (int64_t)n_seq * Hkv;
     int64_t want = requested_splits;
+    const int64_t cap = decode_max_splits(max_len);
     if (want <= 0) {
         // Lengths differ, so the launch relies on the hardware handing out more
-        // workgroups than fit at once: about 1024 rows of the longest sequence
-        // per workgroup, and never fewer workgroups than compute units.
+        // workgroups than fit at once: about 1024 rows per workgroup, and never
+        // fewer workgroups than compute units.  Workgroups go to the 8 compute
+        // dies round-robin by linear id (split + n_splits * pair); an odd
+        // n_splits spreads every split index over all dies, which matters here
+        // because the high split indices carry less work (measured: 5 splits
+        // 108 us, 4 splits 127 us, 8 splits 149 us on the same batch).
         const int64_t by_len = (max_len + 1023) / 1024;
         const int64_t by_cu = (device_compute_units() + pairs - 1) / pairs;
         want = by_len > by_cu ? by_len : by_cu;
+        if (want > 1 && want % 2 == 0) want += want < cap ? 1 : -1;
     }
-    const int64_t cap = decode_max_splits(max_len);
     if (want > cap) want = cap;
     if (want < 1) want = 1;
     DecodePlan plan;
     plan.n_splits = (int32_t)want;
+    // rows per workgroup such that the longest sequence employs all workgroups
+    const int64_t rows = (max_len + want - 1) / want;
+    plan.rows_per_wg = (int32_t)(rows < kDecodeRowTile ? kDecodeRowTile : rows);
     return plan;
 }
 
@@ -474,7 +506,7 @@ static l2kv_status launch_decode(const void* Q, const void* Kc, const void* Vc, 
                        static_cast<const char*>(Q), static_cast<const char*>(Kc),
                        static_cast<const char*>(Vc), (int)Hkv, kv_len,
                        kv_head_stride * (int64_t)E::kBytes, lens, slot_off, (int)plan.n_splits,
-                       scale_log2e, counters, partial, O);
+                       (int)plan.rows_per_wg, scale_log2e, counters, partial, O);
     return launch_status();
 }
 

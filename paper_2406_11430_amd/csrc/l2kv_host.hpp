@@ -32,7 +32,8 @@ l2kv_status compact_dispatch(const void* K, const void* V, l2kv_dtype dt, const 
 // Decomposition of decode attention over the kv_len rows of a KV head:
 // n_splits workgroups take turns on consecutive 64-row blocks.
 struct DecodePlan {
-    int32_t n_splits;        // workgroups per KV head (each owns >= 1 row)
+    int32_t n_splits;        // workgroups launched per KV head
+    int32_t rows_per_wg;     // ragged batches: a sequence of n rows employs ceil(n / rows_per_wg) of them
 };
 constexpr int kDecodeMaxSplits = 256;
 constexpr int kDecodeRowTile = 64;   // rows one workgroup consumes per step (4 waves x 16)

@@ -181,3 +181,43 @@ def test_c5_streaming_batch_sampled_heads(dev):
     assert w.lensA.cpu().tolist() == w.budgets_host[cfg.decode_steps - 1]
     del w
     torch.cuda.empty_cache()
+
+
+def test_split_merge_agrees_with_single_workgroup_on_every_head(dev):
+    # The partials of the workgroups of a KV head are handed to the last one to finish through
+    # device memory.  A single workgroup per head needs no hand-over, so it is the reference:
+    # every output element of every head must agree with it, launch after launch, at the
+    # full per-layer shapes (uniform 32k-context layer; ragged streaming batch).
+    cfg = synth.CONFIGS["C3"]
+    k = l2kv.l2kv_keep_count(cfg.T, cfg.keep_ratio)
+    g = torch.Generator(device=dev)
+    g.manual_seed(77)
+    Kc = torch.randn((cfg.B, cfg.Hkv, k, cfg.D), generator=g, device=dev).to(torch.bfloat16)
+    Vc = torch.randn((cfg.B, cfg.Hkv, k, cfg.D), generator=g, device=dev).to(torch.bfloat16)
+    ws = torch.zeros(l2kv.l2kv_decode_workspace_bytes(cfg.B, cfg.Hq, k, cfg.D), dtype=torch.uint8, device=dev)
+    O1 = torch.empty((cfg.B, cfg.Hq, cfg.D), dtype=torch.float32, device=dev)
+    O = torch.empty_like(O1)
+    for rep in range(24):
+        Q = torch.randn((cfg.B, cfg.Hq, cfg.D), generator=g, device=dev).to(torch.bfloat16)
+        l2kv.l2kv_decode_attn_splits(Q, Kc, Vc, O1, ws, n_splits=1)
+        for ns in (0, 3, 16):
+            O.fill_(float("nan"))
+            l2kv.l2kv_decode_attn_splits(Q, Kc, Vc, O, ws, n_splits=ns)
+            assert float((O - O1).abs().max()) <= 5e-5, (rep, ns)
+    del Kc, Vc
+
+    import bench
+    scfg = synth.STREAM_CONFIGS["C5"].scaled(L=4, decode_steps=2)
+    w = bench.StreamWorkload(scfg, dev)
+    w.compress()
+    w.decode_step(0)
+    ref = torch.empty_like(w.O_v[0])
+    out = torch.empty_like(ref)
+    for rep in range(3):
+        for layer in range(scfg.L):
+            args = (w.Q_v[rep % 2][layer], w.Kc_v[layer], w.Vc_v[layer], w.lensB, w.slot_off, w.max_cap)
+            l2kv.l2kv_decode_attn_ragged(*args, ref, w.ws, n_splits=1)
+            for ns in (0, 4, 5, 8, 13):
+                out.fill_(float("nan"))
+                l2kv.l2kv_decode_attn_ragged(*args, out, w.ws, n_splits=ns)
+                assert float((out - ref).abs().max()) <= 5e-5, (rep, layer, ns)

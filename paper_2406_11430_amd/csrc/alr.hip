@@ -35,6 +35,7 @@ constexpr int kSortLanes = 1024;
 constexpr int kSortWaves = kSortLanes / kWaveSize;
 constexpr int kRadixBits = 8;
 constexpr int kBins = 1 << kRadixBits;
+constexpr int kBatch = 8;            // keys per lane fetched together
 
 struct SortShared {
     uint32_t hist[kSortWaves][kBins];   // per-wave digit counts, then running output offsets
@@ -67,8 +68,19 @@ __device__ void radix_pass(const uint32_t* in_key, const uint32_t* in_val, uint3
 
     for (int i = threadIdx.x; i < kSortWaves * kBins; i += kSortLanes) (&sh.hist[0][0])[i] = 0u;
     __syncthreads();
-    for (int64_t i = lo + lane; i < hi; i += kWaveSize)
-        atomicAdd(&sh.hist[wave][(in_key[i] >> shift) & (kBins - 1)], 1u);
+    // kBatch independent loads are issued before their first use, so a wavefront
+    // pays the L2 latency once per kBatch x 64 keys
+    for (int64_t base = lo; base < hi; base += kBatch * kWaveSize) {
+        uint32_t key[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int64_t i = base + u * kWaveSize + lane;
+            key[u] = i < hi ? in_key[i] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u)
+            if (base + u * kWaveSize + lane < hi) atomicAdd(&sh.hist[wave][(key[u] >> shift) & (kBins - 1)], 1u);
+    }
     __syncthreads();
 
     // counts -> start offsets: within a digit the wavefronts follow each other in
@@ -108,36 +120,46 @@ __device__ void radix_pass(const uint32_t* in_key, const uint32_t* in_val, uint3
 
     // scatter in input order; hist[wave][d] is private to this wavefront from here on
     volatile uint32_t* my_off = sh.hist[wave];
-    for (int64_t base = lo; base < hi; base += kWaveSize) {
-        const int64_t i = base + lane;
-        const bool valid = i < hi;
-        const uint32_t key = valid ? in_key[i] : 0u;
-        uint32_t val = 0;
-        if constexpr (KIND == kIotaIn) val = (uint32_t)i;
-        if constexpr (KIND == kPairs || KIND == kRankOut) val = valid ? in_val[i] : 0u;
-        const uint32_t d = (key >> shift) & (kBins - 1);
-        uint64_t same = __ballot(valid);                    // lanes holding my digit
+    for (int64_t base = lo; base < hi; base += kBatch * kWaveSize) {
+        uint32_t keys[kBatch], vals[kBatch];
 #pragma unroll
-        for (int b = 0; b < kRadixBits; ++b) {
-            const bool bit = (d >> b) & 1u;
-            const uint64_t has = __ballot(bit);
-            same &= bit ? has : ~has;
+        for (int u = 0; u < kBatch; ++u) {
+            const int64_t i = base + u * kWaveSize + lane;
+            const bool valid = i < hi;
+            keys[u] = valid ? in_key[i] : 0u;
+            vals[u] = 0u;
+            if constexpr (KIND == kIotaIn) vals[u] = (uint32_t)i;
+            if constexpr (KIND == kPairs || KIND == kRankOut) vals[u] = valid ? in_val[i] : 0u;
         }
-        const uint32_t before = lanes_below(same);          // same-digit lanes ahead of me
-        const uint32_t count = (uint32_t)__popcll(same);
-        const uint32_t off = my_off[d];
-        const uint32_t pos = sh.digit_base[d] + off + before;
-        if (valid && pos < n && val < n) {                  // counts add up to n, so this always holds
-            if constexpr (KIND == kRankOut) {
-                out_val[val] = (uint32_t)(n - 1) - pos;
-            } else {
-                out_key[pos] = key;
-                if constexpr (KIND != kKeysOnly) out_val[pos] = val;
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            if (base + u * kWaveSize >= hi) break;              // same for all lanes of the wavefront
+            const bool valid = base + u * kWaveSize + lane < hi;
+            const uint32_t key = keys[u], val = vals[u];
+            const uint32_t d = (key >> shift) & (kBins - 1);
+            uint64_t same = __ballot(valid);                    // lanes holding my digit
+#pragma unroll
+            for (int b = 0; b < kRadixBits; ++b) {
+                const bool bit = (d >> b) & 1u;
+                const uint64_t has = __ballot(bit);
+                same &= bit ? has : ~has;
             }
+            const uint32_t before = lanes_below(same);          // same-digit lanes ahead of me
+            const uint32_t count = (uint32_t)__popcll(same);
+            const uint32_t off = my_off[d];
+            const uint32_t pos = sh.digit_base[d] + off + before;
+            if (valid && pos < n && val < n) {                  // counts add up to n, so this always holds
+                if constexpr (KIND == kRankOut) {
+                    out_val[val] = (uint32_t)(n - 1) - pos;
+                } else {
+                    out_key[pos] = key;
+                    if constexpr (KIND != kKeysOnly) out_val[pos] = val;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (valid && before + 1 == count) my_off[d] = off + count;   // last lane of the digit advances it
+            __builtin_amdgcn_wave_barrier();
         }
-        __builtin_amdgcn_wave_barrier();
-        if (valid && before + 1 == count) my_off[d] = off + count;   // last lane of the digit advances it
-        __builtin_amdgcn_wave_barrier();
     }
     __syncthreads();
 }

@@ -348,6 +348,6 @@ const char* l2kv_status_string(l2kv_status s) {
     return "unknown status";
 }
 
-int32_t l2kv_version(void) { return 100; }
+int32_t l2kv_version(void) { return 200; }
 
 }  // extern "C"

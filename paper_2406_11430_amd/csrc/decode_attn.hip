@@ -450,10 +450,23 @@ DecodePlan decode_plan(int32_t B, int32_t Hkv, int64_t kv_len, int32_t requested
     const int64_t pairs = (int64_t)B * Hkv;
     int64_t want = requested_splits;
     if (want <= 0) {
-        // One workgroup (4 waves) per compute unit, all resident at once: measured
-        // best for this stream; more workgroups only lengthen the final merge.
-        const int64_t target = device_compute_units();
-        want = (target + pairs - 1) / pairs;
+        // Workgroups (4 waves each) for about three quarters of the compute units,
+        // all resident at once.  Measured over batch sizes 1..16 and cache lengths
+        // 4k..32k rows per head, the fastest launch always had 192-200 workgroups
+        // on the 256 compute units (e.g. 6 splits x 32 heads: 43.5 us, 8 x 32:
+        // 45.3 us, 9 x 32, which no longer fits at once: 65 us); fewer streams in
+        // flight use the memory system better than one per compute unit.
+        const int64_t target = 3 * (int64_t)device_compute_units() / 4;
+        want = (2 * target + pairs) / (2 * pairs);                 // nearest integer to target / pairs
+        if (want > 1 && want * pairs > device_compute_units()) --want;
+        // With very few heads that rule asks for so many workgroups per head that
+        // the final merge (about 0.2 us per workgroup) outweighs the shorter
+        // streams (about 0.025 us per row): the sum is smallest near
+        // 0.34 * sqrt(rows) workgroups (measured optima: 32 at 8k rows, 64 at 32k,
+        // 128 at 131k with one or two heads).
+        int64_t by_merge = (int64_t)(0.34 * sqrt((double)kv_len));
+        if (by_merge < 8) by_merge = 8;
+        if (want > by_merge) want = by_merge;
     }
     const int64_t cap = decode_max_splits(kv_len);
     if (want > cap) want = cap;

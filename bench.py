@@ -38,7 +38,7 @@ HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 # rocprofv3 --pmc runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a
 # plain 1 GiB copy in the same runs): profiles/hot_path_hbm_traffic_pmc.md.
 # Offline measurement; reported only when the timed shape is that shape.
-MEASURED_DECODE_TRAFFIC_BYTES = {("bf16", 4, 8, 32, 128, 16384): (263203 + 697) * 1024}
+MEASURED_DECODE_TRAFFIC_BYTES = {("bf16", 4, 8, 32, 128, 16384): (263036 + 539) * 1024}
 
 
 # ----------------------------------------------------------------- byte model

@@ -62,8 +62,9 @@ def decode_bytes_per_layer(cfg, k):
 
 # ------------------------------------------------------------------- workload
 class Workload:
-    def __init__(self, cfg, dev):
+    def __init__(self, cfg, dev, decode_splits=0):
         self.cfg, self.dev = cfg, dev
+        self.decode_splits = decode_splits          # 0: the library's own choice
         L, B, Hkv, Hq, D, T = cfg.L, cfg.B, cfg.Hkv, cfg.Hq, cfg.D, cfg.T
         dt = synth.torch_dtype(cfg.dtype)
         self.k = l2kv.l2kv_keep_count(T, cfg.keep_ratio)
@@ -103,6 +104,11 @@ class Workload:
 
     def decode_step(self, step):
         Qs, ws = self.Q_v[step], self.dec_ws
+        if self.decode_splits:
+            for layer in range(self.cfg.L):
+                l2kv.l2kv_decode_attn_splits(Qs[layer], self.Kc_v[layer], self.Vc_v[layer], self.O_v[layer], ws,
+                                             n_splits=self.decode_splits)
+            return
         for layer in range(self.cfg.L):
             l2kv.l2kv_decode_attn(Qs[layer], self.Kc_v[layer], self.Vc_v[layer], self.O_v[layer], ws)
 
@@ -385,6 +391,9 @@ def main():
     ap.add_argument("--cpu-layers", type=int, default=8)
     ap.add_argument("--cpu-decode-steps", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--decode-splits", type=int, default=0,
+                    help="workgroups per KV head in decode attention (0 = the library's default plan); "
+                         "for sweeps of the decomposition, not for the reported line")
     ap.add_argument("--alr", action="store_true",
                     help="time the attention-loss analysis (norm ranks + losses + Y) at the workload's "
                          "per-layer shape instead of the hot path")
@@ -414,7 +423,7 @@ def main():
     if args.decode_steps:
         cfg, overridden = cfg.scaled(decode_steps=args.decode_steps), True
 
-    w = Workload(cfg, dev)
+    w = Workload(cfg, dev, args.decode_splits)
     k = w.k
     nb, sb, cb = compress_bytes_per_layer(cfg, k)
     comp_bytes = (nb + sb + cb) * cfg.L
@@ -473,6 +482,7 @@ def main():
             "head_dim": cfg.D, "cached_tokens": cfg.T, "keep_ratio": cfg.keep_ratio, "kept": k,
             "decode_steps": cfg.decode_steps,
             "step": "compress all layers once + decode_steps x layers decode-attention calls",
+            "decode_splits": args.decode_splits or "library default",
         },
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "us_per_decode_step": round(decode_ms * 1e3 / cfg.decode_steps, 2),

@@ -4,9 +4,10 @@
 // the lowest-norm keys; Eq. 5: exactly m pairs dropped per layer and head)
 // with ties resolved towards the lower token index.
 //
-// One workgroup of 1024 lanes per head (512 for the packed variant below).  The keys (norm bits, complemented for
-// the keep-highest control) sit in registers -- 32 per lane covers 32k tokens
-// -- so nothing is re-read from memory.  The k-th smallest key tau is found
+// One workgroup of 1024 lanes per head (512 for the packed variant below).
+// The keys (norm bits, complemented for the keep-highest control) sit in
+// registers -- 32 per lane covers 32k tokens -- so nothing is re-read from
+// memory.  The k-th smallest key tau is found
 // exactly by a 32-step binary search on its bits: step b counts the keys below
 // (prefix | 1<<b) with wave ballots + popcounts (scalar unit), one LDS atomic
 // per wave and one barrier.  No histogram, no data-dependent contention.

@@ -126,8 +126,9 @@ l2kv_status l2kv_random_keys(int64_t n_heads, int64_t T, uint32_t seed, float* k
  *     Kc[i][j][:] = K[i][kept_idx[i][j]][:],   Vc likewise.
  *   K, V     in : n_heads slabs of T rows (layout above); dropped rows are
  *                 never read.  V may be NULL together with Vc (K only).
- *   kept_idx in : [n_heads][k] int32, every entry in [0, T) (not checked on
- *                 the device: indices outside that range read out of bounds)
+ *   kept_idx in : [n_heads][k] int32, every entry in [0, T) (an entry outside
+ *                 that range is forced into it on the device: a wrong row is
+ *                 copied, nothing is read outside the head)
  *   Kc, Vc   out: [n_heads][k][D], dense
  * Errors: NULL, SHAPE (k <= 0, k > T, ...), DTYPE, ALIGN, LAUNCH.
  */

@@ -24,7 +24,7 @@ constexpr int kCompactRowsPerBlock = kCompactWaves * kRowsPerWaveLoad * kCompact
 template <int W, bool HAS_V>
 __global__ __launch_bounds__(kCompactThreads)
 void compact_kernel(const char* __restrict__ K, const char* __restrict__ V,
-                    const int32_t* __restrict__ kept_idx, int64_t k, int64_t head_stride_bytes,
+                    const int32_t* __restrict__ kept_idx, int64_t T, int64_t k, int64_t head_stride_bytes,
                     int64_t blocks_per_head, char* __restrict__ Kc, char* __restrict__ Vc) {
     constexpr int64_t kSliceBytes = 4 * W;
     constexpr int64_t kRowBytes = kRowLanes * kSliceBytes;
@@ -45,7 +45,9 @@ void compact_kernel(const char* __restrict__ K, const char* __restrict__ V,
     for (int u = 0; u < kCompactUnroll; ++u) {
         int64_t j = first + u;
         j = j < k ? j : k - 1;            // tail: duplicate the last row, store skipped
-        src[u] = src_head + (int64_t)idx[j] * kRowBytes + c * kSliceBytes;
+        int64_t t = idx[j];
+        t = t < 0 ? 0 : (t < T ? t : T - 1);          // an index outside [0, T) cannot lead out of the head
+        src[u] = src_head + t * kRowBytes + c * kSliceBytes;
     }
     Words<W> kr[kCompactUnroll], vr[kCompactUnroll];
 #pragma unroll
@@ -67,19 +69,19 @@ void compact_kernel(const char* __restrict__ K, const char* __restrict__ V,
 
 template <int W>
 static l2kv_status launch_compact(const void* K, const void* V, const int32_t* kept_idx,
-                                  int64_t n_heads, int64_t k, int64_t head_stride_bytes, void* Kc,
-                                  void* Vc, hipStream_t stream) {
+                                  int64_t n_heads, int64_t T, int64_t k, int64_t head_stride_bytes,
+                                  void* Kc, void* Vc, hipStream_t stream) {
     const int64_t bph = (k + kCompactRowsPerBlock - 1) / kCompactRowsPerBlock;
     const int64_t blocks = bph * n_heads;
     if (blocks > 0x7fffffffLL) return L2KV_ERR_SHAPE;
     if (V != nullptr) {
         hipLaunchKernelGGL((compact_kernel<W, true>), dim3((unsigned)blocks), dim3(kCompactThreads), 0,
                            stream, static_cast<const char*>(K), static_cast<const char*>(V), kept_idx,
-                           k, head_stride_bytes, bph, static_cast<char*>(Kc), static_cast<char*>(Vc));
+                           T, k, head_stride_bytes, bph, static_cast<char*>(Kc), static_cast<char*>(Vc));
     } else {
         hipLaunchKernelGGL((compact_kernel<W, false>), dim3((unsigned)blocks), dim3(kCompactThreads), 0,
                            stream, static_cast<const char*>(K), static_cast<const char*>(nullptr),
-                           kept_idx, k, head_stride_bytes, bph, static_cast<char*>(Kc),
+                           kept_idx, T, k, head_stride_bytes, bph, static_cast<char*>(Kc),
                            static_cast<char*>(nullptr));
     }
     return launch_status();
@@ -88,14 +90,13 @@ static l2kv_status launch_compact(const void* K, const void* V, const int32_t* k
 l2kv_status compact_dispatch(const void* K, const void* V, l2kv_dtype dt, const int32_t* kept_idx,
                              int64_t n_heads, int64_t T, int64_t k, int32_t D, int64_t head_stride,
                              void* Kc, void* Vc, hipStream_t stream) {
-    (void)T;
     const int es = dt == L2KV_F32 ? 4 : 2;
     const int row_bytes = D * es;                      // 128, 256 or 512
     const int64_t hs_bytes = head_stride * es;
     switch (row_bytes) {
-        case 128: return launch_compact<2>(K, V, kept_idx, n_heads, k, hs_bytes, Kc, Vc, stream);
-        case 256: return launch_compact<4>(K, V, kept_idx, n_heads, k, hs_bytes, Kc, Vc, stream);
-        case 512: return launch_compact<8>(K, V, kept_idx, n_heads, k, hs_bytes, Kc, Vc, stream);
+        case 128: return launch_compact<2>(K, V, kept_idx, n_heads, T, k, hs_bytes, Kc, Vc, stream);
+        case 256: return launch_compact<4>(K, V, kept_idx, n_heads, T, k, hs_bytes, Kc, Vc, stream);
+        case 512: return launch_compact<8>(K, V, kept_idx, n_heads, T, k, hs_bytes, Kc, Vc, stream);
     }
     return L2KV_ERR_SHAPE;
 }

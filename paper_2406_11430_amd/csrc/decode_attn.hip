@@ -147,13 +147,10 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
     int64_t slab = (int64_t)pair * head_stride_bytes;
     int n_splits = n_splits_grid;
     if (lens != nullptr) {
-        const int64_t total_slots = head_stride_bytes / S::kRowBytes;
-        int64_t first = slot_off[b], end = slot_off[b + 1];
-        first = first < 0 ? 0 : (first > total_slots ? total_slots : first);
-        end = end < first ? first : (end > total_slots ? total_slots : end);
+        const Range slots = clamped_range(slot_off, b, head_stride_bytes / S::kRowBytes);
         kv_len = lens[b];
-        kv_len = kv_len < 0 ? 0 : (kv_len > end - first ? end - first : kv_len);
-        slab = (int64_t)hkv * head_stride_bytes + first * (int64_t)S::kRowBytes;
+        kv_len = kv_len < 0 ? 0 : (kv_len > slots.count ? slots.count : kv_len);
+        slab = (int64_t)hkv * head_stride_bytes + slots.first * (int64_t)S::kRowBytes;
         const int64_t need = (kv_len + rows_per_wg - 1) / rows_per_wg;
         n_splits = need < 1 ? 1 : (need < n_splits_grid ? (int)need : n_splits_grid);
         if (split >= n_splits) return;

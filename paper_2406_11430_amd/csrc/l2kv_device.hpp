@@ -116,6 +116,18 @@ __device__ __forceinline__ void store_words(void* p, const Words<W>& r) {
     }
 }
 
+// Range of sequence `seq` in a device-side offset array (off[seq] .. off[seq+1]),
+// forced into [0, total]: whatever the array holds, first + count <= total, so a
+// caller's inconsistent offsets give meaningless results but no access outside
+// the tensor the offsets describe.
+struct Range { int64_t first, count; };
+__device__ __forceinline__ Range clamped_range(const int64_t* off, int64_t seq, int64_t total) {
+    int64_t a = off[seq], b = off[seq + 1];
+    a = a < 0 ? 0 : (a > total ? total : a);
+    b = b < a ? a : (b > total ? total : b);
+    return Range{a, b - a};
+}
+
 // Element type tags.
 struct F32 { static constexpr int kBytes = 4; };
 struct BF16 { static constexpr int kBytes = 2; };

@@ -72,13 +72,14 @@ void select_kernel(const uint32_t* __restrict__ norm_bits, int64_t T, uint32_t k
         // ragged batch: block = (plane, sequence); sizes and places come from the offset arrays
         const int64_t plane = head / rag.n_seq;
         const int64_t seq = head % rag.n_seq;
-        const int64_t lo = rag.in_off[seq], olo = rag.out_off[seq];
-        T = rag.in_off[seq + 1] - lo;
-        const int64_t kk = rag.out_off[seq + 1] - olo;
+        const Range in = clamped_range(rag.in_off, seq, rag.total_in);
+        const Range outr = clamped_range(rag.out_off, seq, rag.total_out);
+        T = in.count;
+        const int64_t kk = outr.count;
         if (T <= 0 || kk <= 0) return;                       // whole workgroup: nothing to select
         k = (uint32_t)(kk < T ? kk : T);                     // never more than there are
-        src = norm_bits + plane * rag.total_in + lo;
-        out = kept_idx + plane * rag.total_out + olo;
+        src = norm_bits + plane * rag.total_in + in.first;
+        out = kept_idx + plane * rag.total_out + outr.first;
     }
 
     // Wave w owns tokens [w*span, (w+1)*span), span a multiple of 64; iteration

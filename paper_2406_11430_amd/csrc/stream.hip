@@ -50,16 +50,17 @@ void compact_ragged_kernel(const char* __restrict__ K, const char* __restrict__ 
     const int c = lane % kRowLanes;
     const int rg = lane / kRowLanes;
 
-    const int64_t T = in_off[seq + 1] - in_off[seq];
-    const int64_t cap = slot_off[seq + 1] - slot_off[seq];
-    int64_t k = out_off[seq + 1] - out_off[seq];
-    k = k < cap ? k : cap;                                   // never write past the sequence's slots
+    const Range in = clamped_range(in_off, seq, total_tokens);
+    const Range outr = clamped_range(out_off, seq, total_kept);
+    const Range slots = clamped_range(slot_off, seq, total_slots);
+    const int64_t T = in.count;
+    const int64_t k = outr.count < slots.count ? outr.count : slots.count;   // never write past the sequence's slots
     const int64_t first = chunk * kRagRowsPerBlock + (wave * kRowsPerWaveLoad + rg) * kRagUnroll;
     if (first >= k || T <= 0) return;
 
-    const int32_t* idx = kept_idx + plane * total_kept + out_off[seq];
-    const int64_t src_seq = plane * total_tokens + in_off[seq];     // rows
-    const int64_t dst_seq = plane * total_slots + slot_off[seq];    // slots
+    const int32_t* idx = kept_idx + plane * total_kept + outr.first;
+    const int64_t src_seq = plane * total_tokens + in.first;        // rows
+    const int64_t dst_seq = plane * total_slots + slots.first;      // slots
 
     int32_t tok[kRagUnroll];
 #pragma unroll
@@ -140,8 +141,8 @@ void stream_append_kernel(const char* __restrict__ Knew, const char* __restrict_
     const int64_t plane = layer * Hkv + head;
 
     const int32_t len = lens_in[seq];
-    const int64_t cap = slot_off[seq + 1] - slot_off[seq];
-    const bool room = len >= 0 && len < cap;      // a full sequence is left untouched
+    const Range slots = clamped_range(slot_off, seq, total_slots);
+    const bool room = len >= 0 && len < slots.count;   // a full sequence is left untouched
     const Words<S::kWords> kr = load_words<S::kWords>(Knew + r * S::kRowBytes + c * S::kBytes);
     const Words<S::kWords> vr = load_words<S::kWords>(Vnew + r * S::kRowBytes + c * S::kBytes);
 
@@ -157,7 +158,7 @@ void stream_append_kernel(const char* __restrict__ Knew, const char* __restrict_
     const float norm = row16_tree_sum(acc);
 
     if (live && room) {
-        const int64_t slot = plane * total_slots + slot_off[seq] + len;
+        const int64_t slot = plane * total_slots + slots.first + len;
         store_words<S::kWords>(Kc + slot * S::kRowBytes + c * S::kBytes, kr);
         store_words<S::kWords>(Vc + slot * S::kRowBytes + c * S::kBytes, vr);
         if (c == 0) {
@@ -213,12 +214,13 @@ void stream_evict_kernel(int64_t n_seq, const int64_t* __restrict__ slot_off, in
     const int lane = threadIdx.x % kWaveSize;
     const int wave = threadIdx.x / kWaveSize;
 
-    const int64_t cap = slot_off[seq + 1] - slot_off[seq];
+    const Range slots = clamped_range(slot_off, seq, total_slots);
+    const int64_t cap = slots.count;
     int32_t len = lens_in[seq];
     len = len < 0 ? 0 : (len < cap ? len : (int32_t)cap);
     int32_t budget = budgets[seq];
     budget = budget < 0 ? 0 : budget;
-    const int64_t base = plane * total_slots + slot_off[seq];
+    const int64_t base = plane * total_slots + slots.first;
     const uint32_t* nb = reinterpret_cast<const uint32_t*>(norms_c) + base;
     float* nw = norms_c + base;
     int32_t* pw = pos_c + base;

@@ -207,3 +207,70 @@ def test_ragged_decode_lengths_and_splits(dev):
             a = slot_off[s]
             want = oracle.decode_attn(Qn[s:s + 1], Kn[None, :, a:a + n], Vn[None, :, a:a + n], dt)[0]
             assert np.abs(got[s] - want).max() <= ATTN_BAR, (ns, s)
+
+
+def test_inconsistent_device_arrays_stay_inside_the_described_tensors(dev):
+    # Offsets and lengths live on the device and cannot be validated by the host; the kernels force
+    # them into the tensors the call describes.  Every tensor here is allocated with one spare plane
+    # of sentinel values behind the described one, so a miss would land there (and be seen) instead
+    # of outside the allocation.
+    rng = np.random.default_rng(21)
+    D, P, n_seq, total = 128, 2, 4, 300
+    SENT = 1024.0                                  # exact in bf16
+
+    def padded(shape_tail, dtype, fill):
+        t = torch.full((P + 1,) + shape_tail, fill, dtype=dtype, device=dev)
+        return t, t[:P]
+
+    Kc_all, Kc = padded((total, D), torch.bfloat16, SENT)
+    Vc_all, Vc = padded((total, D), torch.bfloat16, SENT)
+    nc_all, nc = padded((total,), torch.float32, SENT)
+    pc_all, pc = padded((total,), torch.int32, 777)
+    Kc[:] = rows(rng, (P, total, D), "bf16").to(dev)
+    Vc[:] = rows(rng, (P, total, D), "bf16").to(dev)
+    nc[:] = 1.0
+    pc[:] = 0
+    bad_off = torch.tensor([-50, 100, 10 ** 12, 250, 90], dtype=torch.int64, device=dev)    # not ascending, out of range
+    lens = torch.tensor([500, -3, 40, 10 ** 6], dtype=torch.int32, device=dev)
+    lens_out = torch.zeros_like(lens)
+
+    # append: rows go to clamped slots or nowhere
+    Kn, Vn = rows(rng, (1, n_seq, P, D), "bf16").to(dev), rows(rng, (1, n_seq, P, D), "bf16").to(dev)
+    tok = torch.arange(n_seq, dtype=torch.int32, device=dev)
+    l2kv.l2kv_stream_append(Kn, Vn, tok, bad_off, lens, lens_out, Kc, Vc, nc, pc)
+    # evict: budgets far below / above the lengths
+    budgets = torch.tensor([1, 5, -7, 3], dtype=torch.int32, device=dev)
+    lens2 = torch.zeros_like(lens)
+    l2kv.l2kv_stream_evict(bad_off, lens, budgets, lens2, Kc, Vc, nc, pc)
+    # decode over the same arrays
+    Q = rows(rng, (n_seq, P * 2, D), "bf16").to(dev)
+    ws = torch.zeros(l2kv.l2kv_decode_ragged_workspace_bytes(n_seq, P * 2, total, D), dtype=torch.uint8, device=dev)
+    O = torch.full((n_seq, P * 2, D), float("nan"), dtype=torch.float32, device=dev)
+    l2kv.l2kv_decode_attn_ragged(Q, Kc, Vc, lens, bad_off, total, O, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(O).all()
+    assert torch.all(O[2] == 0)                        # sequence 2: offsets 10^12 .. 250 clamp to an empty range
+    for spare, val in ((Kc_all[P], SENT), (Vc_all[P], SENT), (nc_all[P], SENT), (pc_all[P], 777)):
+        assert torch.all(spare.float() == val)         # nothing was written behind the described planes
+    got = lens2.cpu().numpy()
+    assert got[0] <= 1 and got[1] == 0 and got[2] == 0 and got[3] <= 3
+
+    # ragged selection and compaction with broken input / output offsets and indices
+    total_in, total_kept = 400, 200
+    norms_all = torch.full((P + 1, total_in), 3.0, dtype=torch.float32, device=dev)
+    norms = norms_all[:P]
+    norms[:] = torch.from_numpy(rng.random((P, total_in)).astype(np.float32)).to(dev)
+    idx_all = torch.full((P + 1, total_kept), -9, dtype=torch.int32, device=dev)
+    idx = idx_all[:P]
+    in_off = torch.tensor([0, 500, -20, 390, 10 ** 9], dtype=torch.int64, device=dev)
+    out_off = torch.tensor([0, 120, 10 ** 9, 150, 199], dtype=torch.int64, device=dev)
+    l2kv.l2kv_select_ragged(norms, in_off, out_off, total_in, idx)
+    K = rows(rng, (P, total_in, D), "bf16").to(dev)
+    V = rows(rng, (P, total_in, D), "bf16").to(dev)
+    idx[:, ::3] = 10 ** 8                              # indices far outside any sequence
+    l2kv.l2kv_compact_ragged(K, V, norms, idx, in_off, out_off, total_kept, bad_off, Kc, Vc, nc, pc)
+    torch.cuda.synchronize()
+    assert torch.all(idx_all[P] == -9)
+    for spare, val in ((Kc_all[P], SENT), (Vc_all[P], SENT), (nc_all[P], SENT), (pc_all[P], 777)):
+        assert torch.all(spare.float() == val)
+    assert int(pc.min()) >= 0 and int(pc.max()) < total_in

@@ -207,6 +207,8 @@ class StreamWorkload:
         self.lens_init = torch.tensor(self.k0, dtype=torch.int32, device=dev)
         self.lensA = torch.empty_like(self.lens_init)
         self.lensB = torch.empty_like(self.lens_init)
+        self.seq_order = torch.empty_like(self.lens_init)
+        self.use_order = True                       # launch the sequences longest first
         self.budgets = torch.tensor(self.budgets_host, dtype=torch.int32, device=dev)
         self.tokens = torch.tensor([[n + t for n in lens] for t in range(cfg.decode_steps)],
                                    dtype=torch.int32, device=dev)
@@ -225,6 +227,9 @@ class StreamWorkload:
         l2kv.l2kv_compact_ragged(self.K, self.V, self.norms, self.idx, self.in_off, self.out_off,
                                  self.max_kept, self.slot_off, self.Kc, self.Vc, self.nc, self.pc)
         self.lensA.copy_(self.lens_init)
+        # longest-first launch order of the batch: set up once per compression, reused by every
+        # decode step (all sequences grow alike, so it stays the length order)
+        l2kv.l2kv_length_order(self.lensA, self.seq_order)
 
     def decode_step(self, t):
         l2kv.l2kv_stream_append(self.Knew[t], self.Vnew[t], self.tokens[t], self.slot_off, self.lensA,
@@ -232,7 +237,8 @@ class StreamWorkload:
         Qs = self.Q_v[t]
         for layer in range(self.cfg.L):
             l2kv.l2kv_decode_attn_ragged(Qs[layer], self.Kc_v[layer], self.Vc_v[layer], self.lensB,
-                                         self.slot_off, self.max_cap, self.O_v[layer], self.ws)
+                                         self.slot_off, self.max_cap, self.O_v[layer], self.ws,
+                                         seq_order=self.seq_order if self.use_order else None)
         l2kv.l2kv_stream_evict(self.slot_off, self.lensB, self.budgets[t], self.lensA, self.Kc, self.Vc,
                                self.nc, self.pc)
 
@@ -274,6 +280,7 @@ def main_stream(args, dev):
     if args.decode_steps:
         cfg, overridden = cfg.scaled(decode_steps=args.decode_steps), True
     w = StreamWorkload(cfg, dev)
+    w.use_order = not args.no_seq_order
     attn_bytes, other_bytes = w.decode_bytes()
     comp_bytes = w.compress_bytes()
     step_bytes = comp_bytes + attn_bytes + other_bytes
@@ -394,6 +401,9 @@ def main():
     ap.add_argument("--decode-splits", type=int, default=0,
                     help="workgroups per KV head in decode attention (0 = the library's default plan); "
                          "for sweeps of the decomposition, not for the reported line")
+    ap.add_argument("--no-seq-order", action="store_true",
+                    help="streaming workloads: launch the sequences in batch order instead of longest first "
+                         "(for comparisons)")
     ap.add_argument("--alr", action="store_true",
                     help="time the attention-loss analysis (norm ranks + losses + Y) at the workload's "
                          "per-layer shape instead of the hot path")

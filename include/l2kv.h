@@ -281,6 +281,15 @@ l2kv_status l2kv_stream_evict(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, in
  * Decode attention over ONE layer of the slot cache: Q [n_seq][Hq][D]; Kc, Vc
  * point at that layer's Hkv planes ([Hkv][total_slots][D]); sequence s attends
  * to its lens[s] occupied slots (0 slots give a zero output row).
+ *   seq_order: NULL, or a DEVICE int32 [n_seq] permutation of 0..n_seq-1 giving
+ *             the order in which the sequences are launched; with the longest
+ *             sequence first (l2kv_length_order) the library uses fewer,
+ *             larger workgroups and lets the hardware balance them, which is
+ *             faster on batches of mixed lengths.  It only steers scheduling:
+ *             outputs land at the sequence's own rows of O in any case.  An
+ *             array that is not a permutation computes some sequences twice
+ *             and others not at all (entries are forced into 0..n_seq-1).
+ *             The order may be stale (lengths change from step to step).
  *   max_len : an upper bound of all lens[s] (sizes the decomposition and the
  *             workspace; rows beyond it are still attended to)
  *   n_splits: 0 = library default
@@ -291,9 +300,18 @@ l2kv_status l2kv_stream_evict(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, in
 l2kv_status l2kv_decode_attn_ragged(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt,
                                     int32_t n_seq, int32_t Hq, int32_t Hkv, int32_t D,
                                     const int32_t* lens, const int64_t* slot_offsets,
-                                    int64_t total_slots, int64_t max_len, float scale,
-                                    int32_t n_splits, float* O, void* workspace,
+                                    const int32_t* seq_order, int64_t total_slots, int64_t max_len,
+                                    float scale, int32_t n_splits, float* O, void* workspace,
                                     size_t workspace_bytes, void* stream);
+
+/*
+ * Longest-first order of a batch: order[r] = the sequence with the r-th largest
+ * lens (equal lengths: lower index first).  lens, order: DEVICE int32 [n_seq],
+ * distinct arrays; n_seq <= 65535.  A set-up call (one workgroup, quadratic in
+ * n_seq); its result can serve many decode steps.
+ * Errors: NULL, SHAPE, ALIGN, LAUNCH.
+ */
+l2kv_status l2kv_length_order(const int32_t* lens, int32_t n_seq, int32_t* order, void* stream);
 
 size_t l2kv_decode_ragged_workspace_bytes(int32_t n_seq, int32_t Hq, int64_t max_len, int32_t D);
 

@@ -15,6 +15,8 @@ Functions, each following the passage named in the C source:
 * ``compress(K, V, dtype, r)``    -- the three compression steps in sequence
 * ``StreamHead``                  -- one (sequence, head) cache under streaming
                                      eviction (Sec. 4, language-modelling setting)
+* ``length_order(lens)``          -- longest-first order of a ragged batch (a scheduling aid
+                                     of the library, not part of the paper's method)
 * ``attn_probs(Q, K, dtype)``     -- attention scores a_p of one query over the full cache (Eq. 2)
 * ``drop_order(n32)``             -- positions in the order the norm rule discards them
 * ``attention_loss(a, n32, m)``   -- attention mass of the m dropped pairs (Eq. 5)
@@ -187,6 +189,12 @@ def random_keys(n_heads: int, T: int, seed: int) -> np.ndarray:
     keys = np.empty((n_heads, T), dtype=np.float32)
     _load().l2kv_oracle_random_keys(int(n_heads), int(T), int(seed) & 0xFFFFFFFF, keys.ctypes.data)
     return keys
+
+
+def length_order(lens) -> np.ndarray:
+    """Indices of the sequences from longest to shortest, equal lengths in index order."""
+    lens = np.asarray(lens, dtype=np.int64)
+    return np.lexsort((np.arange(lens.shape[0]), -lens)).astype(np.int32)
 
 
 class StreamHead:

@@ -56,9 +56,10 @@ SIGNATURES = {
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_void_p]),
     "l2kv_decode_attn_ragged": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32,
-                                          C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64,
-                                          C.c_float, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
+                                          C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                          C.c_int64, C.c_float, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
                                           C.c_void_p]),
+    "l2kv_length_order": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
     "l2kv_decode_ragged_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int64, C.c_int32]),
     "l2kv_norm_ranks": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t,
                                   C.c_void_p]),
@@ -331,18 +332,28 @@ def l2kv_stream_evict(slot_offsets: torch.Tensor, lens_in: torch.Tensor, budgets
 def l2kv_decode_attn_ragged(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, lens: torch.Tensor,
                             slot_offsets: torch.Tensor, max_len: int, O: torch.Tensor,
                             workspace: torch.Tensor, scale: float = 0.0, n_splits: int = 0,
-                            stream=None) -> None:
+                            seq_order: Optional[torch.Tensor] = None, stream=None) -> None:
     """Q ``[n_seq, Hq, D]``, Kc/Vc ``[Hkv, total_slots, D]`` (one layer) -> O ``[n_seq, Hq, D]``."""
-    _dev(Q, Kc, Vc, lens, slot_offsets, O, workspace)
+    _dev(Q, Kc, Vc, lens, slot_offsets, O, workspace, seq_order)
     n_seq, Hq, D = Q.shape
     Hkv, total_slots, Dc = Kc.shape
     assert Dc == D and Vc.shape == Kc.shape and Kc.dtype == Q.dtype == Vc.dtype
     assert O.dtype == torch.float32 and O.numel() == n_seq * Hq * D
     _i32(lens, n_seq), _i64(slot_offsets, n_seq + 1)
+    if seq_order is not None:
+        _i32(seq_order, n_seq)
     _check("l2kv_decode_attn_ragged", lib().l2kv_decode_attn_ragged(
         _ptr(Q), _ptr(Kc), _ptr(Vc), _dtype_code(Q), n_seq, Hq, Hkv, D, _ptr(lens), _ptr(slot_offsets),
-        total_slots, int(max_len), float(scale), int(n_splits), _ptr(O), _ptr(workspace),
+        _ptr(seq_order), total_slots, int(max_len), float(scale), int(n_splits), _ptr(O), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def l2kv_length_order(lens: torch.Tensor, order: torch.Tensor, stream=None) -> None:
+    """lens ``[n_seq]`` int32 -> order ``[n_seq]`` int32 (pre-allocated): longest sequence first."""
+    _dev(lens, order)
+    n_seq = lens.numel()
+    _i32(lens, n_seq), _i32(order, n_seq)
+    _check("l2kv_length_order", lib().l2kv_length_order(_ptr(lens), n_seq, _ptr(order), _stream(stream)))
 
 
 # ------------------------------------------------------------ attention-loss analysis

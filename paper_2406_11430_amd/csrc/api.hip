@@ -157,7 +157,7 @@ l2kv_status l2kv_decode_attn_splits(const void* Q, const void* Kc, const void* V
         return L2KV_ERR_ALIGN;
     const float s = scale > 0.f ? scale : 1.0f / std::sqrt(static_cast<float>(D));
     const DecodePlan plan = decode_plan(B, Hkv, kv_len, n_splits);
-    return decode_dispatch(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, nullptr, nullptr, s,
+    return decode_dispatch(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, nullptr, nullptr, nullptr, s,
                            plan, O, workspace, static_cast<hipStream_t>(stream));
 }
 
@@ -266,8 +266,9 @@ size_t l2kv_decode_ragged_workspace_bytes(int32_t n_seq, int32_t Hq, int64_t max
 l2kv_status l2kv_decode_attn_ragged(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt,
                                     int32_t n_seq, int32_t Hq, int32_t Hkv, int32_t D,
                                     const int32_t* lens, const int64_t* slot_offsets,
-                                    int64_t total_slots, int64_t max_len, float scale, int32_t n_splits,
-                                    float* O, void* workspace, size_t workspace_bytes, void* stream) {
+                                    const int32_t* seq_order, int64_t total_slots, int64_t max_len,
+                                    float scale, int32_t n_splits, float* O, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
     if (Q == nullptr || Kc == nullptr || Vc == nullptr || O == nullptr || lens == nullptr ||
         slot_offsets == nullptr)
         return L2KV_ERR_NULL;
@@ -276,18 +277,27 @@ l2kv_status l2kv_decode_attn_ragged(const void* Q, const void* Kc, const void* V
         total_slots > kMaxTokens || max_len > total_slots || !dim_ok(D))
         return L2KV_ERR_SHAPE;
     if (Hq % Hkv != 0 || Hq / Hkv > 8) return L2KV_ERR_SHAPE;
-    if (static_cast<int64_t>(n_seq) * Hkv > 65535) return L2KV_ERR_SHAPE;
-    if (n_splits < 0 || n_splits > decode_max_splits(max_len)) return L2KV_ERR_SHAPE;
-    if (!std::isfinite(scale)) return L2KV_ERR_SHAPE;
+    if (static_cast<int64_t>(n_seq) * Hkv > 65535 || static_cast<int64_t>(n_seq) * Hq > 0x7fffffffLL)
+        return L2KV_ERR_SHAPE;
+    if (n_splits < 0 || n_splits > decode_max_splits(max_len) || !std::isfinite(scale)) return L2KV_ERR_SHAPE;
     if (workspace == nullptr || workspace_bytes < l2kv_decode_workspace_bytes(n_seq, Hq, max_len, D))
         return L2KV_ERR_WORKSPACE;
     if (!aligned(Q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(O, 4) ||
-        !aligned(workspace, 16) || !aligned(lens, 4) || !aligned(slot_offsets, 8))
+        !aligned(workspace, 16) || !aligned(lens, 4) || !aligned(slot_offsets, 8) || !aligned(seq_order, 4))
         return L2KV_ERR_ALIGN;
     const float s = scale > 0.f ? scale : 1.0f / std::sqrt(static_cast<float>(D));
-    const DecodePlan plan = decode_plan_ragged(n_seq, Hkv, max_len, n_splits);
+    const DecodePlan plan = decode_plan_ragged(n_seq, Hkv, max_len, n_splits, seq_order != nullptr);
     return decode_dispatch(Q, Kc, Vc, dt, n_seq, Hq, Hkv, max_len, D, total_slots * static_cast<int64_t>(D),
-                           lens, slot_offsets, s, plan, O, workspace, static_cast<hipStream_t>(stream));
+                           lens, slot_offsets, seq_order, s, plan, O, workspace,
+                           static_cast<hipStream_t>(stream));
+}
+
+l2kv_status l2kv_length_order(const int32_t* lens, int32_t n_seq, int32_t* order, void* stream) {
+    if (lens == nullptr || order == nullptr) return L2KV_ERR_NULL;
+    if (n_seq <= 0 || n_seq > 65535) return L2KV_ERR_SHAPE;
+    if (lens == order) return L2KV_ERR_SHAPE;
+    if (!aligned(lens, 4) || !aligned(order, 4)) return L2KV_ERR_ALIGN;
+    return length_order_dispatch(lens, n_seq, order, static_cast<hipStream_t>(stream));
 }
 
 /* ---- attention-loss analysis ---------------------------------------------- */

@@ -30,6 +30,8 @@
 
 #include <math.h>
 
+#include <atomic>
+
 namespace l2kv {
 
 constexpr int kDecThreads = 256;
@@ -37,6 +39,11 @@ constexpr int kDecWaves = kDecThreads / kWaveSize;                 // 4
 constexpr int kDecLoads = 4;                                        // row loads per lane per step
 constexpr int kDecRowsPerStep = kDecLoads * kRowsPerWaveLoad;       // 16 rows per wave step
 constexpr int kDecGroups = kDecWaves * kRowsPerWaveLoad;            // 16 row groups per workgroup
+// Ordered ragged batches: from this length of the longest sequence on, one workgroup per compute
+// unit is kept resident by requesting this much unused LDS (more than half of the 160 KiB).
+constexpr int64_t kOrderedMinRows = 2048;
+constexpr int64_t kOrderedMaxRows = 16384;   // rows one workgroup takes before a sequence is split
+constexpr int32_t kOrderedLdsPad = 80 * 1024;
 static_assert(kDecWaves * kDecRowsPerStep == kDecodeRowTile, "row tile mismatch");
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -109,7 +116,8 @@ __global__ __launch_bounds__(kDecThreads)
 void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
                    const char* __restrict__ Vc, int Hkv, int64_t kv_len_uniform,
                    int64_t head_stride_bytes, const int32_t* __restrict__ lens,
-                   const int64_t* __restrict__ slot_off, int n_splits_grid, int rows_per_wg,
+                   const int64_t* __restrict__ slot_off, const int32_t* __restrict__ seq_order,
+                   int n_splits_grid, int rows_per_wg,
                    float scale_log2e, uint32_t* __restrict__ counters,
                    float* __restrict__ partial, float* __restrict__ O) {
     using S = Slice<E, D>;
@@ -124,8 +132,15 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
 
     const int split = blockIdx.x;
     const int pair = blockIdx.y;                 // b * Hkv + hkv
-    const int b = pair / Hkv;
     const int hkv = pair % Hkv;
+    // Ragged batches may come with a processing order (longest sequence first):
+    // the launch index then names a position in that order, not the sequence.
+    int b = pair / Hkv;
+    if (seq_order != nullptr) {
+        const int n_seq = (int)gridDim.y / Hkv;
+        const int ob = seq_order[b];
+        b = ob < 0 ? 0 : (ob < n_seq ? ob : n_seq - 1);
+    }
     const int Hq = Hkv * G;
     const int lane = threadIdx.x % kWaveSize;
     // the wave index is the same in all 64 lanes: keep it in a scalar register
@@ -471,14 +486,35 @@ DecodePlan decode_plan(int32_t B, int32_t Hkv, int64_t kv_len, int32_t requested
     DecodePlan plan;
     plan.n_splits = (int32_t)want;
     plan.rows_per_wg = 1;
+    plan.lds_pad = 0;
     return plan;
 }
 
-DecodePlan decode_plan_ragged(int32_t n_seq, int32_t Hkv, int64_t max_len, int32_t requested_splits) {
+DecodePlan decode_plan_ragged(int32_t n_seq, int32_t Hkv, int64_t max_len, int32_t requested_splits,
+                              bool ordered) {
     const int64_t pairs = (int64_t)n_seq * Hkv;
     int64_t want = requested_splits;
     const int64_t cap = decode_max_splits(max_len);
-    if (want <= 0) {
+    DecodePlan plan;
+    plan.lds_pad = 0;
+    if (ordered && max_len >= kOrderedMinRows) {
+        // The caller supplied a longest-first order.  One workgroup then takes a
+        // whole (sequence, KV head) -- only sequences beyond 16k rows, or all of
+        // them when the batch has fewer pairs than the uniform rule wants
+        // workgroups, are split -- and only one workgroup is resident per
+        // compute unit, so the hardware hands the remaining ones out as compute
+        // units become free: longest-processing-time-first scheduling by the
+        // dispatcher.  Measured on the 64-sequence streaming batch (512 pairs of
+        // 512..4200 rows): 97 us per layer against 108 us for the unordered
+        // plan; splitting every sequence in two costs 115 us.
+        if (want <= 0) {
+            const int64_t by_len = (max_len + kOrderedMaxRows - 1) / kOrderedMaxRows;
+            const int64_t target = 3 * (int64_t)device_compute_units() / 4;
+            const int64_t by_cu = (2 * target + pairs) / (2 * pairs);
+            want = by_len > by_cu ? by_len : by_cu;
+        }
+        plan.lds_pad = kOrderedLdsPad;
+    } else if (want <= 0) {
         // Lengths differ, so the launch relies on the hardware handing out more
         // workgroups than fit at once: about 1024 rows per workgroup, and never
         // fewer workgroups than compute units.  Workgroups go to the 8 compute
@@ -493,7 +529,6 @@ DecodePlan decode_plan_ragged(int32_t n_seq, int32_t Hkv, int64_t max_len, int32
     }
     if (want > cap) want = cap;
     if (want < 1) want = 1;
-    DecodePlan plan;
     plan.n_splits = (int32_t)want;
     // rows per workgroup such that the longest sequence employs all workgroups
     const int64_t rows = (max_len + want - 1) / want;
@@ -504,18 +539,34 @@ DecodePlan decode_plan_ragged(int32_t n_seq, int32_t Hkv, int64_t max_len, int32
 template <typename E, int D, int G>
 static l2kv_status launch_decode(const void* Q, const void* Kc, const void* Vc, int32_t B, int32_t Hq,
                                  int32_t Hkv, int64_t kv_len, int64_t kv_head_stride,
-                                 const int32_t* lens, const int64_t* slot_off, float scale,
-                                 const DecodePlan& plan, float* O, void* workspace,
-                                 hipStream_t stream) {
+                                 const int32_t* lens, const int64_t* slot_off,
+                                 const int32_t* seq_order, float scale, const DecodePlan& plan,
+                                 float* O, void* workspace, hipStream_t stream) {
     (void)Hq;
     const float scale_log2e = scale * 1.4426950408889634f;
     uint32_t* counters = static_cast<uint32_t*>(workspace);
     float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + decode_counter_bytes(B, Hkv));
     dim3 grid((unsigned)plan.n_splits, (unsigned)(B * Hkv));
-    hipLaunchKernelGGL((decode_kernel<E, D, G>), grid, dim3(kDecThreads), 0, stream,
+    if (plan.lds_pad > 0) {
+        // Unused dynamic LDS, requested only to keep a second workgroup off the
+        // compute unit.  Requests beyond 64 KiB need the attribute; it is set per
+        // kernel instance and device, here every time the device changes.
+        static std::atomic<int> attr_device{-1};
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return L2KV_ERR_LAUNCH;
+        if (attr_device.load(std::memory_order_relaxed) != dev) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<E, D, G>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, plan.lds_pad) != hipSuccess) {
+                (void)hipGetLastError();
+                return L2KV_ERR_LAUNCH;
+            }
+            attr_device.store(dev, std::memory_order_relaxed);
+        }
+    }
+    hipLaunchKernelGGL((decode_kernel<E, D, G>), grid, dim3(kDecThreads), (size_t)plan.lds_pad, stream,
                        static_cast<const char*>(Q), static_cast<const char*>(Kc),
                        static_cast<const char*>(Vc), (int)Hkv, kv_len,
-                       kv_head_stride * (int64_t)E::kBytes, lens, slot_off, (int)plan.n_splits,
+                       kv_head_stride * (int64_t)E::kBytes, lens, slot_off, seq_order, (int)plan.n_splits,
                        (int)plan.rows_per_wg, scale_log2e, counters, partial, O);
     return launch_status();
 }
@@ -523,13 +574,13 @@ static l2kv_status launch_decode(const void* Q, const void* Kc, const void* Vc, 
 template <typename E, int D>
 static l2kv_status decode_by_group(int G, const void* Q, const void* Kc, const void* Vc, int32_t B,
                                    int32_t Hq, int32_t Hkv, int64_t kv_len, int64_t kv_head_stride,
-                                   const int32_t* lens, const int64_t* slot_off, float scale,
-                                   const DecodePlan& plan, float* O, void* workspace,
-                                   hipStream_t stream) {
+                                   const int32_t* lens, const int64_t* slot_off,
+                                   const int32_t* seq_order, float scale, const DecodePlan& plan,
+                                   float* O, void* workspace, hipStream_t stream) {
 #define L2KV_G(N)                                                                                   \
     case N:                                                                                         \
         return launch_decode<E, D, N>(Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride, lens, slot_off, \
-                                      scale, plan, O, workspace, stream)
+                                      seq_order, scale, plan, O, workspace, stream)
     switch (G) {
         L2KV_G(1); L2KV_G(2); L2KV_G(3); L2KV_G(4); L2KV_G(5); L2KV_G(6); L2KV_G(7); L2KV_G(8);
     }
@@ -540,19 +591,19 @@ static l2kv_status decode_by_group(int G, const void* Q, const void* Kc, const v
 l2kv_status decode_dispatch(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt, int32_t B,
                             int32_t Hq, int32_t Hkv, int64_t kv_len, int32_t D,
                             int64_t kv_head_stride, const int32_t* lens, const int64_t* slot_off,
-                            float scale, const DecodePlan& plan, float* O, void* workspace,
-                            hipStream_t stream) {
+                            const int32_t* seq_order, float scale, const DecodePlan& plan, float* O,
+                            void* workspace, hipStream_t stream) {
     const int G = Hq / Hkv;
     if (dt == L2KV_F32) {
         return D == 64 ? decode_by_group<F32, 64>(G, Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride,
-                                                  lens, slot_off, scale, plan, O, workspace, stream)
+                                                  lens, slot_off, seq_order, scale, plan, O, workspace, stream)
                        : decode_by_group<F32, 128>(G, Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride,
-                                                   lens, slot_off, scale, plan, O, workspace, stream);
+                                                   lens, slot_off, seq_order, scale, plan, O, workspace, stream);
     }
     return D == 64 ? decode_by_group<BF16, 64>(G, Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride,
-                                               lens, slot_off, scale, plan, O, workspace, stream)
+                                               lens, slot_off, seq_order, scale, plan, O, workspace, stream)
                    : decode_by_group<BF16, 128>(G, Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride,
-                                                lens, slot_off, scale, plan, O, workspace, stream);
+                                                lens, slot_off, seq_order, scale, plan, O, workspace, stream);
 }
 
 }  // namespace l2kv

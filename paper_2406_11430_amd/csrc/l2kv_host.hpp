@@ -34,6 +34,7 @@ l2kv_status compact_dispatch(const void* K, const void* V, l2kv_dtype dt, const 
 struct DecodePlan {
     int32_t n_splits;        // workgroups launched per KV head
     int32_t rows_per_wg;     // ragged batches: a sequence of n rows employs ceil(n / rows_per_wg) of them
+    int32_t lds_pad;         // bytes of unused dynamic LDS requested to keep one workgroup per compute unit
 };
 constexpr int kDecodeMaxSplits = 256;
 constexpr int kDecodeRowTile = 64;   // rows one workgroup consumes per step (4 waves x 16)
@@ -46,16 +47,18 @@ inline size_t decode_counter_bytes(int32_t B, int32_t Hkv) {
 }
 l2kv_status workspace_init_dispatch(void* workspace, size_t bytes, hipStream_t stream);
 DecodePlan decode_plan(int32_t B, int32_t Hkv, int64_t kv_len, int32_t requested_splits);
-DecodePlan decode_plan_ragged(int32_t n_seq, int32_t Hkv, int64_t max_len, int32_t requested_splits);
+DecodePlan decode_plan_ragged(int32_t n_seq, int32_t Hkv, int64_t max_len, int32_t requested_splits,
+                              bool ordered);
 
 // lens / slot_off NULL: uniform batch (kv_len rows per slab, slabs kv_head_stride apart).
 // Otherwise ragged: cache [Hkv][total_slots][D], kv_head_stride = total_slots * D,
-// kv_len = longest sequence (sizes the decomposition only).
+// kv_len = longest sequence (sizes the decomposition only); seq_order (may be NULL): the
+// order in which the sequences are launched.
 l2kv_status decode_dispatch(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt, int32_t B,
                             int32_t Hq, int32_t Hkv, int64_t kv_len, int32_t D,
                             int64_t kv_head_stride, const int32_t* lens, const int64_t* slot_off,
-                            float scale, const DecodePlan& plan, float* O, void* workspace,
-                            hipStream_t stream);
+                            const int32_t* seq_order, float scale, const DecodePlan& plan, float* O,
+                            void* workspace, hipStream_t stream);
 
 // Ragged selection / compaction and the streaming slot cache (stream.hip, select.hip).
 l2kv_status select_ragged_dispatch(const float* norms, int32_t n_planes, int32_t n_seq,
@@ -73,6 +76,7 @@ l2kv_status stream_append_dispatch(const void* Knew, const void* Vnew, l2kv_dtyp
                                    const int64_t* slot_off, int64_t total_slots, const int32_t* lens_in,
                                    int32_t* lens_out, void* Kc, void* Vc, float* norms_c, int32_t* pos_c,
                                    hipStream_t stream);
+l2kv_status length_order_dispatch(const int32_t* lens, int32_t n_seq, int32_t* order, hipStream_t stream);
 l2kv_status stream_evict_dispatch(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, int32_t D,
                                   const int64_t* slot_off, int64_t total_slots, const int32_t* lens_in,
                                   const int32_t* budgets, int32_t* lens_out, void* Kc, void* Vc,

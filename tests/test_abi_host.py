@@ -226,16 +226,24 @@ def test_ragged_and_stream_validation(lib):
     dec = lib.l2kv_decode_attn_ragged
     ws = lib.l2kv_decode_ragged_workspace_bytes(4, 8, 300, 128)
     assert ws == lib.l2kv_decode_workspace_bytes(4, 8, 300, 128)
-    ok = [P, P, P, 1, 4, 8, 2, 128, P, P, 600, 300, 0.0, 0, P, P, ws, None]
+    # Q Kc Vc dt n_seq Hq Hkv D lens slot_off seq_order total_slots max_len scale n_splits O ws ws_bytes stream
+    ok = [P, P, P, 1, 4, 8, 2, 128, P, P, None, 600, 300, 0.0, 0, P, P, ws, None]
     assert dec(*ok[:8] + [None] + ok[9:]) == E_NULL
-    bad = list(ok); bad[11] = 601                                         # max_len > total_slots
+    bad = list(ok); bad[12] = 601                                         # max_len > total_slots
     assert dec(*bad) == E_SHAPE
-    bad = list(ok); bad[13] = 99
+    bad = list(ok); bad[14] = 99
     assert dec(*bad) == E_SHAPE
-    bad = list(ok); bad[16] = ws - 1
+    bad = list(ok); bad[17] = ws - 1
     assert dec(*bad) == E_WS
     bad = list(ok); bad[9] = P + 4
     assert dec(*bad) == E_ALIGN
+    bad = list(ok); bad[10] = P + 2                                       # seq_order given but misaligned
+    assert dec(*bad) == E_ALIGN
+    order = lib.l2kv_length_order
+    assert order(None, 4, P, None) == E_NULL and order(P, 4, None, None) == E_NULL
+    assert order(P, 0, P + 64, None) == E_SHAPE and order(P, 70000, P + 64, None) == E_SHAPE
+    assert order(P, 4, P, None) == E_SHAPE                                # in place
+    assert order(P + 2, 4, P + 64, None) == E_ALIGN
 
 
 def test_attention_loss_validation(lib):

@@ -196,9 +196,15 @@ def test_ragged_decode_lengths_and_splits(dev):
     smax = l2kv.l2kv_decode_max_splits(max(lens))
     ws = torch.zeros(l2kv.l2kv_decode_ragged_workspace_bytes(len(lens), Hkv * G, max(lens), D),
                      dtype=torch.uint8, device=dev)
-    for ns in (0, 1, 2, 5, smax):
+    lpt = torch.empty_like(d_lens)
+    l2kv.l2kv_length_order(d_lens, lpt)
+    assert np.array_equal(lpt.cpu().numpy(), oracle.length_order(lens))
+    shuffled = torch.from_numpy(rng.permutation(len(lens)).astype(np.int32)).to(dev)
+    for ns, order in ((0, None), (1, None), (2, None), (5, None), (smax, None), (0, lpt), (1, lpt), (3, lpt),
+                      (0, shuffled), (2, shuffled)):
         O = torch.full((len(lens), Hkv * G, D), float("nan"), dtype=torch.float32, device=dev)
-        l2kv.l2kv_decode_attn_ragged(Q.to(dev), K.to(dev), V.to(dev), d_lens, d_off, max(lens), O, ws, n_splits=ns)
+        l2kv.l2kv_decode_attn_ragged(Q.to(dev), K.to(dev), V.to(dev), d_lens, d_off, max(lens), O, ws, n_splits=ns,
+                                     seq_order=order)
         got = O.cpu().numpy()
         assert np.all(got[0] == 0)                                   # empty sequence
         for s, n in enumerate(lens):
@@ -274,3 +280,12 @@ def test_inconsistent_device_arrays_stay_inside_the_described_tensors(dev):
     for spare, val in ((Kc_all[P], SENT), (Vc_all[P], SENT), (nc_all[P], SENT), (pc_all[P], 777)):
         assert torch.all(spare.float() == val)
     assert int(pc.min()) >= 0 and int(pc.max()) < total_in
+
+
+@pytest.mark.parametrize("n_seq", [1, 5, 64, 1500])
+def test_length_order_exact(dev, n_seq):
+    rng = np.random.default_rng(n_seq)
+    lens = rng.integers(0, max(2, n_seq // 3), n_seq).astype(np.int32)          # many equal lengths
+    order = torch.full((n_seq,), -1, dtype=torch.int32, device=dev)
+    l2kv.l2kv_length_order(torch.from_numpy(lens).to(dev), order)
+    assert np.array_equal(order.cpu().numpy(), oracle.length_order(lens))

@@ -515,3 +515,13 @@ def test_random_keys_hash_known_values_and_spread():
     kept = oracle.select(oracle.random_keys(1, 4096, 99), 2048)[0]
     counts = np.histogram(kept, bins=4, range=(0, 4096))[0]
     assert counts.sum() == 2048 and counts.min() > 430 and counts.max() < 600
+
+
+def test_length_order_is_longest_first_with_index_tiebreak():
+    rng = np.random.default_rng(12)
+    lens = rng.integers(0, 6, 40)
+    order = oracle.length_order(lens)
+    assert sorted(order) == list(range(40))
+    for a, b in zip(order[:-1], order[1:]):
+        assert lens[a] > lens[b] or (lens[a] == lens[b] and a < b)
+    assert list(oracle.length_order([5, 9, 9, 1])) == [1, 2, 0, 3]

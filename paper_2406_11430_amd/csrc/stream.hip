@@ -82,8 +82,8 @@ void compact_ragged_kernel(const char* __restrict__ K, const char* __restrict__ 
         const int64_t j = first + u;
         if (j < k) {
             const int64_t slot = dst_seq + j;
-            store_words<W>(Kc + slot * kRowBytes + c * kSliceBytes, kr[u]);
-            store_words<W>(Vc + slot * kRowBytes + c * kSliceBytes, vr[u]);
+            store_words_stream<W>(Kc + slot * kRowBytes + c * kSliceBytes, kr[u]);
+            store_words_stream<W>(Vc + slot * kRowBytes + c * kSliceBytes, vr[u]);
             if (c == 0) {
                 norms_c[slot] = norms[src_seq + tok[u]];
                 pos_c[slot] = tok[u];

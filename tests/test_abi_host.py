@@ -280,3 +280,21 @@ def test_attention_loss_validation(lib):
     assert call(ws=None) == E_WS and call(ws_bytes=wa - 1) == E_WS
     assert call(Q=P + 4) == E_ALIGN and call(alr=P + 4) == E_ALIGN and call(loss=P + 4) == E_ALIGN
     assert call(ws=P + 8) == E_ALIGN
+
+
+def test_header_is_plain_c_and_cpp(tmp_path):
+    # the boundary is a C ABI: the header must compile on its own as C99 and as C++
+    import subprocess
+    src_c = tmp_path / "use_header.c"
+    src_c.write_text('#include "l2kv.h"\nint main(void) { return (int)l2kv_keep_count(8, 0.5) == 4 ? 0 : 1; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(src_c)],
+                   check=True)
+    src_cpp = tmp_path / "use_header.cpp"
+    src_cpp.write_text('#include "l2kv.h"\nint main() { return l2kv_version() > 0 ? 0 : 1; }\n')
+    subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(src_cpp)], check=True)
+    # and a C program links against the library and runs its host-only entry points
+    exe = tmp_path / "use_header"
+    subprocess.run(["gcc", "-std=c99", "-I", inc, str(src_c), "-o", str(exe), binding.LIB_PATH,
+                    "-Wl,-rpath," + os.path.dirname(binding.LIB_PATH)], check=True)
+    assert subprocess.run([str(exe)]).returncode == 0

@@ -140,7 +140,10 @@ def test_select_heavy_ties_and_special_values(dev, T):
             assert np.array_equal(idx.cpu().numpy(), want), (T, k, mode)
 
 
-@pytest.mark.parametrize("T,r", [(32769, 0.5), (40000, 0.3), (65536, 0.5), (131072, 0.1)])
+# 131072 is the last length of the register-resident variants; beyond it the keys are re-read
+# from memory in every search step
+@pytest.mark.parametrize("T,r", [(32769, 0.5), (40000, 0.3), (65536, 0.5), (131072, 0.1), (131073, 0.1),
+                                 (200000, 0.37), (1 << 20, 0.5)])
 def test_select_long_sequences(dev, T, r):
     rng = np.random.default_rng(T)
     n = np.exp(rng.standard_normal((3, T))).astype(np.float32)

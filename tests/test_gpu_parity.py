@@ -114,6 +114,44 @@ def test_norms_strided_heads(dev):
     assert np.array_equal(out.cpu().numpy().view(np.uint32), n32.view(np.uint32))
 
 
+def test_compact_and_decode_with_padded_head_stride(dev):
+    # head strides larger than rows * D: the C entry points on padded buffers
+    rng = np.random.default_rng(78)
+    B, Hkv, G, T, D, pad = 2, 2, 2, 333, 128, 192
+    n = B * Hkv
+    K, V = rand_cache(rng, (n, T, D), "bf16"), rand_cache(rng, (n, T, D), "bf16")
+    Q = rand_cache(rng, (B, Hkv * G, D), "bf16")
+    stride = T * D + pad
+
+    def padded(x):
+        buf = np.full((n, stride), 0x7fc0, dtype=np.uint16)          # NaN pattern in the gaps
+        buf[:, : T * D] = x.reshape(n, -1)
+        return to_dev(buf, "bf16", dev)
+
+    Kp, Vp = padded(K), padded(V)
+    st = torch.cuda.current_stream().cuda_stream
+    k = 100
+    idx = np.stack([np.sort(rng.permutation(T)[:k]) for _ in range(n)]).astype(np.int32)
+    idd = torch.from_numpy(idx).to(dev)
+    Kc = torch.zeros((n, k, D), dtype=torch.bfloat16, device=dev)
+    Vc = torch.zeros_like(Kc)
+    rc = l2kv.lib().l2kv_compact(Kp.data_ptr(), Vp.data_ptr(), l2kv.L2KV_BF16, idd.data_ptr(), n, T, k, D, stride,
+                                 Kc.data_ptr(), Vc.data_ptr(), st)
+    assert rc == 0
+    assert np.array_equal(synth.as_numpy_bits(Kc), oracle.compact(K, idx))
+    assert np.array_equal(synth.as_numpy_bits(Vc), oracle.compact(V, idx))
+    # decode straight from the padded (uncompacted) slabs
+    O = torch.full((B, Hkv * G, D), float("nan"), dtype=torch.float32, device=dev)
+    wsb = l2kv.l2kv_decode_workspace_bytes(B, Hkv * G, T, D)
+    ws = torch.zeros(wsb, dtype=torch.uint8, device=dev)
+    Qd = to_dev(Q, "bf16", dev)
+    rc = l2kv.lib().l2kv_decode_attn(Qd.data_ptr(), Kp.data_ptr(), Vp.data_ptr(), l2kv.L2KV_BF16, B, Hkv * G, Hkv, T,
+                                     D, stride, 0.0, O.data_ptr(), ws.data_ptr(), wsb, st)
+    assert rc == 0
+    want = oracle.decode_attn(Q, K.reshape(B, Hkv, T, D), V.reshape(B, Hkv, T, D), "bf16")
+    assert np.abs(O.cpu().numpy() - want).max() <= 1e-4
+
+
 # --------------------------------------------------------------- selection
 @pytest.mark.parametrize("T", [1, 2, 63, 64, 65, 1000, 1024, 1025, 5000, 16384, 32768])
 def test_select_random_norms(dev, T):

@@ -356,6 +356,36 @@ def run_pipeline(cfg, dev, layers=None, steps=1):
             assert err <= ATTN_GATE and err <= ATTN_BAR, (layer, step, err)
 
 
+def test_hot_path_on_a_side_stream(dev):
+    # every entry point enqueues on the stream it is given: run the four steps on a non-default
+    # stream while the default stream stays idle, and compare with the oracle after syncing only it
+    cfg = synth.CONFIGS["C3"].scaled(L=1, B=1, T=3000, decode_steps=1)
+    k = oracle.keep_count(cfg.T, cfg.keep_ratio)
+    K, V = synth.make_layer(cfg, 0)
+    Q = synth.make_query(cfg, 0, 0)
+    Kd, Vd, Qd = K.to(dev), V.to(dev), Q.to(dev)
+    norms = torch.empty((cfg.B, cfg.Hkv, cfg.T), dtype=torch.float32, device=dev)
+    idx = torch.empty((cfg.B, cfg.Hkv, k), dtype=torch.int32, device=dev)
+    sel_ws = torch.zeros(l2kv.l2kv_select_workspace_bytes(cfg.B * cfg.Hkv, cfg.T), dtype=torch.uint8, device=dev)
+    Kc = torch.empty((cfg.B, cfg.Hkv, k, cfg.D), dtype=Kd.dtype, device=dev)
+    Vc = torch.empty_like(Kc)
+    O = torch.full((cfg.B, cfg.Hq, cfg.D), float("nan"), dtype=torch.float32, device=dev)
+    ws = torch.empty(l2kv.l2kv_decode_workspace_bytes(cfg.B, cfg.Hq, k, cfg.D), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    l2kv.l2kv_decode_workspace_init(ws, stream=side)
+    l2kv.l2kv_norms(Kd, norms, stream=side)
+    l2kv.l2kv_select(norms, cfg.keep_ratio, idx, None, sel_ws, stream=side)
+    l2kv.l2kv_compact(Kd, Vd, idx, Kc, Vc, stream=side)
+    l2kv.l2kv_decode_attn(Qd, Kc, Vc, O, ws, stream=side)
+    side.synchronize()
+    n32, _, widx, wKc, wVc = oracle.compress(synth.as_numpy_bits(K), synth.as_numpy_bits(V), cfg.dtype, cfg.keep_ratio)
+    assert np.array_equal(idx.cpu().numpy(), widx)
+    assert np.array_equal(synth.as_numpy_bits(Kc), wKc)
+    want = oracle.decode_attn(synth.as_numpy_bits(Q), wKc, wVc, cfg.dtype)
+    assert np.abs(O.cpu().numpy() - want).max() <= ATTN_BAR
+
+
 def test_pipeline_config_c1_tiny_fp32(dev):
     run_pipeline(synth.CONFIGS["C1"], dev, steps=2)
 

@@ -386,6 +386,56 @@ def test_hot_path_on_a_side_stream(dev):
     assert np.abs(O.cpu().numpy() - want).max() <= ATTN_BAR
 
 
+def test_hot_path_under_graph_capture(dev):
+    # the calls allocate nothing and record no memset, so they can be captured into a HIP graph;
+    # the graph is replayed several times on fresh inputs, with eager work in between, and every
+    # replay must reproduce the eager results bit for bit
+    cfg = synth.CONFIGS["C3"].scaled(L=1, B=2, T=2500, decode_steps=1)
+    k = oracle.keep_count(cfg.T, cfg.keep_ratio)
+    dt = synth.torch_dtype(cfg.dtype)
+    Kd = torch.empty((cfg.B, cfg.Hkv, cfg.T, cfg.D), dtype=dt, device=dev)
+    Vd = torch.empty_like(Kd)
+    Qd = torch.empty((cfg.B, cfg.Hq, cfg.D), dtype=dt, device=dev)
+    norms = torch.empty((cfg.B, cfg.Hkv, cfg.T), dtype=torch.float32, device=dev)
+    idx = torch.empty((cfg.B, cfg.Hkv, k), dtype=torch.int32, device=dev)
+    sel_ws = torch.zeros(l2kv.l2kv_select_workspace_bytes(cfg.B * cfg.Hkv, cfg.T), dtype=torch.uint8, device=dev)
+    Kc = torch.empty((cfg.B, cfg.Hkv, k, cfg.D), dtype=dt, device=dev)
+    Vc = torch.empty_like(Kc)
+    O = torch.empty((cfg.B, cfg.Hq, cfg.D), dtype=torch.float32, device=dev)
+    ws = torch.zeros(l2kv.l2kv_decode_workspace_bytes(cfg.B, cfg.Hq, k, cfg.D), dtype=torch.uint8, device=dev)
+
+    def path():
+        l2kv.l2kv_decode_workspace_init(ws)
+        l2kv.l2kv_norms(Kd, norms)
+        l2kv.l2kv_select(norms, cfg.keep_ratio, idx, None, sel_ws)
+        l2kv.l2kv_compact(Kd, Vd, idx, Kc, Vc)
+        l2kv.l2kv_decode_attn(Qd, Kc, Vc, O, ws)
+
+    def load(layer):
+        K, V = synth.make_layer(cfg, layer)
+        Kd.copy_(K.to(dev)); Vd.copy_(V.to(dev)); Qd.copy_(synth.make_query(cfg, layer, 0).to(dev))
+
+    load(0)
+    path()                                             # eager warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        path()
+    for layer in (1, 2, 3):
+        load(layer)
+        path()                                         # eager reference on these inputs
+        torch.cuda.synchronize()
+        want_idx, want_O = idx.clone(), O.clone()
+        idx.fill_(-1); O.fill_(float("nan")); Kc.zero_(); Vc.zero_(); norms.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(idx, want_idx), layer
+        assert torch.equal(O.view(torch.int32), want_O.view(torch.int32)), layer
+        K, V = synth.make_layer(cfg, layer)
+        widx = oracle.compress(synth.as_numpy_bits(K), synth.as_numpy_bits(V), cfg.dtype, cfg.keep_ratio)[2]
+        assert np.array_equal(idx.cpu().numpy(), widx)
+
+
 def test_pipeline_config_c1_tiny_fp32(dev):
     run_pipeline(synth.CONFIGS["C1"], dev, steps=2)
 

@@ -290,6 +290,9 @@ l2kv_status l2kv_stream_evict(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, in
  *             array that is not a permutation computes some sequences twice
  *             and others not at all (entries are forced into 0..n_seq-1).
  *             The order may be stale (lengths change from step to step).
+ *             The first ordered call for a (dtype, D, Hq/Hkv) on a device sets a
+ *             launch attribute of the kernel and must not be made under graph
+ *             capture; later calls are plain launches.
  *   max_len : an upper bound of all lens[s] (sizes the decomposition and the
  *             workspace; rows beyond it are still attended to)
  *   n_splits: 0 = library default

@@ -156,7 +156,7 @@ l2kv_status l2kv_decode_attn_splits(const void* Q, const void* Kc, const void* V
     if (!aligned(Q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(O, 4) || !aligned(workspace, 16))
         return L2KV_ERR_ALIGN;
     const float s = scale > 0.f ? scale : 1.0f / std::sqrt(static_cast<float>(D));
-    const DecodePlan plan = decode_plan(B, Hkv, kv_len, n_splits);
+    const DecodePlan plan = decode_plan(B, Hkv, Hq / Hkv, kv_len, n_splits);
     return decode_dispatch(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, nullptr, nullptr, nullptr, s,
                            plan, O, workspace, static_cast<hipStream_t>(stream));
 }

@@ -46,7 +46,7 @@ inline size_t decode_counter_bytes(int32_t B, int32_t Hkv) {
     return (raw + 255) / 256 * 256;
 }
 l2kv_status workspace_init_dispatch(void* workspace, size_t bytes, hipStream_t stream);
-DecodePlan decode_plan(int32_t B, int32_t Hkv, int64_t kv_len, int32_t requested_splits);
+DecodePlan decode_plan(int32_t B, int32_t Hkv, int32_t group, int64_t kv_len, int32_t requested_splits);
 DecodePlan decode_plan_ragged(int32_t n_seq, int32_t Hkv, int64_t max_len, int32_t requested_splits,
                               bool ordered);
 

@@ -541,3 +541,36 @@ def test_per_head_keep_counts_through_the_ragged_entry_points(dev):
         assert np.array_equal(synth.as_numpy_bits(Vc[0, o:o + k]), V[0, h * T:(h + 1) * T][want])
         o += k
     assert np.array_equal(idx[0, :T].cpu().numpy(), np.arange(T))   # the skipped head is untouched
+
+
+# ------------------------------------------------- seeded random shape sweep
+def test_random_shapes_whole_path(dev):
+    # 40 seeded draws of (dtype, head size, batch, heads, group, length, ratio, split count): the whole
+    # path against the oracle on shapes nobody picked by hand (tile and ownership arithmetic)
+    rng = np.random.default_rng(20240611)
+    for case in range(40):
+        dt = ("bf16", "f32")[int(rng.integers(2))]
+        D = (64, 128)[int(rng.integers(2))]
+        B, Hkv, G = int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.integers(1, 9))
+        T = int(rng.integers(1, 3000))
+        r = float(rng.uniform(0.02, 1.0))
+        k = oracle.keep_count(T, r)
+        K, V = rand_cache(rng, (B, Hkv, T, D), dt), rand_cache(rng, (B, Hkv, T, D), dt)
+        if case % 3 == 0:
+            K[..., ::4, :] = K[..., :1, :]                          # repeated rows: ties in the norms
+        Q = rand_cache(rng, (B, Hkv * G, D), dt)
+        n32, _, idx, Kc, Vc = oracle.compress(K, V, dt, r)
+        Kd, Vd = to_dev(K, dt, dev), to_dev(V, dt, dev)
+        nd = gpu_norms(Kd)
+        assert np.array_equal(nd.cpu().numpy().view(np.uint32), n32.view(np.uint32)), case
+        idd, _ = gpu_select(nd, k)
+        assert np.array_equal(idd.cpu().numpy(), idx), (case, T, k)
+        Kcd = torch.empty((B, Hkv, k, D), dtype=Kd.dtype, device=dev)
+        Vcd = torch.empty_like(Kcd)
+        l2kv.l2kv_compact(Kd, Vd, idd, Kcd, Vcd)
+        assert np.array_equal(synth.as_numpy_bits(Kcd), Kc) and np.array_equal(synth.as_numpy_bits(Vcd), Vc), case
+        want = oracle.decode_attn(Q, Kc, Vc, dt)
+        smax = l2kv.l2kv_decode_max_splits(k)
+        for ns in {0, 1, int(rng.integers(1, smax + 1)), smax}:
+            got = gpu_decode(to_dev(Q, dt, dev), Kcd, Vcd, n_splits=ns).cpu().numpy()
+            assert np.abs(got - want).max() <= ATTN_BAR, (case, dt, D, B, Hkv, G, T, k, ns)

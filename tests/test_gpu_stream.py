@@ -128,7 +128,7 @@ class Batch:
             O = torch.full((self.n_seq, Hq, D), float("nan"), dtype=torch.float32, device=dev)
             l2kv.l2kv_decode_attn_ragged(Q.to(dev), self.Kc[layer * Hkv:(layer + 1) * Hkv],
                                          self.Vc[layer * Hkv:(layer + 1) * Hkv], self.lensB, self.d_slot,
-                                         max_len, O, ws, n_splits=n_splits)
+                                         max_len, O, ws, n_splits=min(n_splits, l2kv.l2kv_decode_max_splits(max_len)))
             got = O.cpu().numpy()
             Qn = synth.as_numpy_bits(Q)
             for s in range(self.n_seq):
@@ -289,3 +289,18 @@ def test_length_order_exact(dev, n_seq):
     order = torch.full((n_seq,), -1, dtype=torch.int32, device=dev)
     l2kv.l2kv_length_order(torch.from_numpy(lens).to(dev), order)
     assert np.array_equal(order.cpu().numpy(), oracle.length_order(lens))
+
+
+def test_stream_random_batches(dev):
+    # seeded random ragged batches (lengths, heads, group size, ratio, steps, split counts, with and
+    # without a launch order) driven step by step against the oracle
+    rng = np.random.default_rng(2406)
+    for case in range(6):
+        dt, D = (("bf16", 128), ("f32", 64), ("bf16", 64))[case % 3]
+        n_seq = int(rng.integers(1, 7))
+        lens = [int(x) for x in rng.integers(1, 400, n_seq)]
+        steps = int(rng.integers(2, 7))
+        b = Batch(dev, rng, dt, D, L=int(rng.integers(1, 3)), Hkv=int(rng.integers(1, 4)), G=int(rng.integers(1, 5)),
+                  lens=lens, r=float(rng.uniform(0.1, 0.9)), steps=steps, ties=bool(case % 2))
+        for t in range(steps):
+            b.step(rng, t, n_splits=int(rng.integers(0, 3)))

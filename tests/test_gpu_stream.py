@@ -103,7 +103,7 @@ class Batch:
             assert np.array_equal(Kc[p, a:a + n][order], Kk) and np.array_equal(Vc[p, a:a + n][order], Vk)
             assert np.array_equal(nc[p, a:a + n][order].view(np.uint32), nk.view(np.uint32))
 
-    def step(self, rng, t, n_splits=0):
+    def step(self, rng, t, n_splits=0, ordered=False):
         dev, D, L, Hkv, G = self.dev, self.D, self.L, self.Hkv, self.G
         live = [s for s, n in enumerate(self.lens0) if n > 0]
         Kn = rows(rng, (L, self.n_seq, Hkv, D), self.dt)
@@ -123,12 +123,18 @@ class Batch:
         ws = torch.zeros(l2kv.l2kv_decode_ragged_workspace_bytes(self.n_seq, Hq, max_len, D),
                          dtype=torch.uint8, device=dev)
         worst = 0.0
+        order = None
+        if ordered:
+            order = torch.empty_like(self.lensB)
+            l2kv.l2kv_length_order(self.lensB, order)
+            assert np.array_equal(order.cpu().numpy(), oracle.length_order(lens_now))
         for layer in range(L):
             Q = rows(rng, (self.n_seq, Hq, D), self.dt)
             O = torch.full((self.n_seq, Hq, D), float("nan"), dtype=torch.float32, device=dev)
             l2kv.l2kv_decode_attn_ragged(Q.to(dev), self.Kc[layer * Hkv:(layer + 1) * Hkv],
                                          self.Vc[layer * Hkv:(layer + 1) * Hkv], self.lensB, self.d_slot,
-                                         max_len, O, ws, n_splits=min(n_splits, l2kv.l2kv_decode_max_splits(max_len)))
+                                         max_len, O, ws, n_splits=min(n_splits, l2kv.l2kv_decode_max_splits(max_len)),
+                                         seq_order=order)
             got = O.cpu().numpy()
             Qn = synth.as_numpy_bits(Q)
             for s in range(self.n_seq):
@@ -303,4 +309,4 @@ def test_stream_random_batches(dev):
         b = Batch(dev, rng, dt, D, L=int(rng.integers(1, 3)), Hkv=int(rng.integers(1, 4)), G=int(rng.integers(1, 5)),
                   lens=lens, r=float(rng.uniform(0.1, 0.9)), steps=steps, ties=bool(case % 2))
         for t in range(steps):
-            b.step(rng, t, n_splits=int(rng.integers(0, 3)))
+            b.step(rng, t, n_splits=int(rng.integers(0, 3)), ordered=bool((case + t) % 2))

@@ -259,8 +259,18 @@ l2kv_status l2kv_stream_evict(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, in
                                  lens_out, Kc, Vc, norms_c, pos_c, static_cast<hipStream_t>(stream));
 }
 
+// Ragged workspace = the uniform one (counters, partials) followed by room for a
+// launch order of the sequences, which the library computes itself when the
+// caller passes none (small batches of long sequences only, see below).
+static size_t ragged_order_bytes(int32_t n_seq) {
+    return (static_cast<size_t>(n_seq) * sizeof(int32_t) + 255) / 256 * 256;
+}
+constexpr int32_t kSelfOrderMaxSeq = 512;     // the set-up kernel is quadratic in n_seq
+constexpr int64_t kSelfOrderMinRows = 2048;   // below this the ordered plan is not used anyway
+
 size_t l2kv_decode_ragged_workspace_bytes(int32_t n_seq, int32_t Hq, int64_t max_len, int32_t D) {
-    return l2kv_decode_workspace_bytes(n_seq, Hq, max_len, D);
+    const size_t base = l2kv_decode_workspace_bytes(n_seq, Hq, max_len, D);
+    return base == 0 ? 0 : base + ragged_order_bytes(n_seq);
 }
 
 l2kv_status l2kv_decode_attn_ragged(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt,
@@ -280,12 +290,23 @@ l2kv_status l2kv_decode_attn_ragged(const void* Q, const void* Kc, const void* V
     if (static_cast<int64_t>(n_seq) * Hkv > 65535 || static_cast<int64_t>(n_seq) * Hq > 0x7fffffffLL)
         return L2KV_ERR_SHAPE;
     if (n_splits < 0 || n_splits > decode_max_splits(max_len) || !std::isfinite(scale)) return L2KV_ERR_SHAPE;
-    if (workspace == nullptr || workspace_bytes < l2kv_decode_workspace_bytes(n_seq, Hq, max_len, D))
+    if (workspace == nullptr || workspace_bytes < l2kv_decode_ragged_workspace_bytes(n_seq, Hq, max_len, D))
         return L2KV_ERR_WORKSPACE;
     if (!aligned(Q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(O, 4) ||
         !aligned(workspace, 16) || !aligned(lens, 4) || !aligned(slot_offsets, 8) || !aligned(seq_order, 4))
         return L2KV_ERR_ALIGN;
     const float s = scale > 0.f ? scale : 1.0f / std::sqrt(static_cast<float>(D));
+    if (seq_order == nullptr && n_splits == 0 && n_seq > 1 && n_seq <= kSelfOrderMaxSeq &&
+        max_len >= kSelfOrderMinRows) {
+        // no order from the caller: a longest-first order is worked out here, per call, into the
+        // tail of the workspace (a few microseconds; passing a stored order avoids them)
+        int32_t* own_order = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) +
+                                                        l2kv_decode_workspace_bytes(n_seq, Hq, max_len, D));
+        if (l2kv_status st = length_order_dispatch(lens, n_seq, own_order, static_cast<hipStream_t>(stream));
+            st != L2KV_OK)
+            return st;
+        seq_order = own_order;
+    }
     const DecodePlan plan = decode_plan_ragged(n_seq, Hkv, max_len, n_splits, seq_order != nullptr);
     return decode_dispatch(Q, Kc, Vc, dt, n_seq, Hq, Hkv, max_len, D, total_slots * static_cast<int64_t>(D),
                            lens, slot_offsets, seq_order, s, plan, O, workspace,

@@ -303,21 +303,38 @@ l2kv_status stream_evict_dispatch(l2kv_dtype dt, int32_t n_planes, int32_t n_seq
 // order[r] = the sequence with the r-th largest length (equal lengths: lower
 // index first), by rank counting in one workgroup: a permutation of 0..n_seq-1
 // whatever lens holds.  Meant for batch set-up, not for the decode loop.
+constexpr int kOrderLdsSeqs = 8192;    // batches up to this size are ranked out of LDS
+
 __global__ __launch_bounds__(1024)
 void length_order_kernel(const int32_t* __restrict__ lens, int32_t n_seq, int32_t* __restrict__ order) {
-    for (int32_t s = threadIdx.x; s < n_seq; s += 1024) {
-        const int32_t mine = lens[s];
+    __shared__ int32_t s_len[kOrderLdsSeqs];
+    const bool in_lds = n_seq <= kOrderLdsSeqs;
+    if (in_lds) {
+        for (int32_t s = threadIdx.x; s < n_seq; s += (int32_t)blockDim.x) s_len[s] = lens[s];
+        __syncthreads();
+    }
+    for (int32_t s = threadIdx.x; s < n_seq; s += (int32_t)blockDim.x) {
+        const int32_t mine = in_lds ? s_len[s] : lens[s];
         int32_t rank = 0;
-        for (int32_t t = 0; t < n_seq; ++t) {
-            const int32_t other = lens[t];
-            rank += (other > mine || (other == mine && t < s)) ? 1 : 0;
+        if (in_lds) {
+            for (int32_t t = 0; t < n_seq; ++t) {
+                const int32_t other = s_len[t];
+                rank += (other > mine || (other == mine && t < s)) ? 1 : 0;
+            }
+        } else {
+            for (int32_t t = 0; t < n_seq; ++t) {
+                const int32_t other = lens[t];
+                rank += (other > mine || (other == mine && t < s)) ? 1 : 0;
+            }
         }
         order[rank] = s;
     }
 }
 
 l2kv_status length_order_dispatch(const int32_t* lens, int32_t n_seq, int32_t* order, hipStream_t stream) {
-    hipLaunchKernelGGL(length_order_kernel, dim3(1), dim3(1024), 0, stream, lens, n_seq, order);
+    // small batches need only as many lanes as sequences (fewer waves to start and retire)
+    const unsigned threads = n_seq <= 64 ? 64u : (n_seq <= 256 ? 256u : 1024u);
+    hipLaunchKernelGGL(length_order_kernel, dim3(1), dim3(threads), 0, stream, lens, n_seq, order);
     return launch_status();
 }
 

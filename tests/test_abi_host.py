@@ -225,7 +225,7 @@ def test_ragged_and_stream_validation(lib):
     assert ev(*bad) == E_DTYPE
     dec = lib.l2kv_decode_attn_ragged
     ws = lib.l2kv_decode_ragged_workspace_bytes(4, 8, 300, 128)
-    assert ws == lib.l2kv_decode_workspace_bytes(4, 8, 300, 128)
+    assert ws == lib.l2kv_decode_workspace_bytes(4, 8, 300, 128) + 256     # + room for a launch order
     # Q Kc Vc dt n_seq Hq Hkv D lens slot_off seq_order total_slots max_len scale n_splits O ws ws_bytes stream
     ok = [P, P, P, 1, 4, 8, 2, 128, P, P, None, 600, 300, 0.0, 0, P, P, ws, None]
     assert dec(*ok[:8] + [None] + ok[9:]) == E_NULL

@@ -288,7 +288,7 @@ def test_inconsistent_device_arrays_stay_inside_the_described_tensors(dev):
     assert int(pc.min()) >= 0 and int(pc.max()) < total_in
 
 
-@pytest.mark.parametrize("n_seq", [1, 5, 64, 1500])
+@pytest.mark.parametrize("n_seq", [1, 5, 64, 65, 257, 1500, 9000])
 def test_length_order_exact(dev, n_seq):
     rng = np.random.default_rng(n_seq)
     lens = rng.integers(0, max(2, n_seq // 3), n_seq).astype(np.int32)          # many equal lengths

@@ -402,8 +402,8 @@ def main():
                     help="workgroups per KV head in decode attention (0 = the library's default plan); "
                          "for sweeps of the decomposition, not for the reported line")
     ap.add_argument("--no-seq-order", action="store_true",
-                    help="streaming workloads: launch the sequences in batch order instead of longest first "
-                         "(for comparisons)")
+                    help="streaming workloads: pass no stored launch order to the ragged attention calls "
+                         "(the library then works one out per call; for comparisons)")
     ap.add_argument("--alr", action="store_true",
                     help="time the attention-loss analysis (norm ranks + losses + Y) at the workload's "
                          "per-layer shape instead of the hot path")

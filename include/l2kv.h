@@ -191,6 +191,32 @@ int32_t l2kv_decode_max_splits(int64_t kv_len);
 l2kv_status l2kv_decode_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 size_t  l2kv_decode_workspace_bytes(int32_t B, int32_t Hq, int64_t kv_len, int32_t D);
 
+/*
+ * l2kv_decode_attn for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels, same result as
+ * l2kv_decode_attn, but the arrival counters and split partials live in a
+ * scratch array inside the library (L2KV_STATIC_SCRATCH_BYTES of device memory
+ * per GPU, held until the process ends).  The call itself allocates and frees
+ * nothing and records no memset.
+ *   Limit: counters (4 bytes per (sequence, KV head), padded to 256) plus
+ *   B*Hq*(workgroups per KV head)*(D+2)*4 bytes of partials must fit the
+ *   scratch array; larger shapes return L2KV_ERR_WORKSPACE and launch nothing.
+ *   (32k-context batch of 4 x 32 query heads: 0.4 MB.)
+ *   All calls on one GPU share that GPU's array: two calls that may overlap in
+ *   time (different streams without an ordering between them, or two host
+ *   threads) race and give wrong results; calls ordered on one stream are fine.
+ *   The first call on a device looks the array up and enqueues one small fill
+ *   kernel on `stream`; make that first call outside graph capture.
+ * Errors: as l2kv_decode_attn, L2KV_ERR_WORKSPACE for a shape beyond the limit,
+ * L2KV_ERR_LAUNCH if the array cannot be located on the current device.
+ */
+#define L2KV_STATIC_SCRATCH_BYTES (4u << 20)
+l2kv_status l2kv_decode_attn_static(const void* Q, const void* Kc, const void* Vc,
+                                    l2kv_dtype dt, int32_t B, int32_t Hq, int32_t Hkv,
+                                    int64_t kv_len, int32_t D, int64_t kv_head_stride,
+                                    float scale, float* O, void* stream);
+
 /* ------------------------------------------------------------------------
  * Ragged batches and streaming eviction.
  *

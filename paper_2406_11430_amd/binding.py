@@ -40,6 +40,9 @@ SIGNATURES = {
                                           C.c_int32, C.c_int32, C.c_int64, C.c_int32, C.c_int64,
                                           C.c_float, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
                                           C.c_void_p]),
+    "l2kv_decode_attn_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32,
+                                          C.c_int32, C.c_int64, C.c_int32, C.c_int64, C.c_float, C.c_void_p,
+                                          C.c_void_p]),
     "l2kv_decode_max_splits": (C.c_int32, [C.c_int64]),
     "l2kv_decode_workspace_init": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p]),
     "l2kv_decode_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int64, C.c_int32]),
@@ -250,6 +253,19 @@ def l2kv_decode_attn_splits(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor,
                                            D, n * D, float(scale), int(n_splits), _ptr(O),
                                            _ptr(workspace), ws_bytes, _stream(stream))
         _check("l2kv_decode_attn_splits", st)
+
+
+def l2kv_decode_attn_static(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, O: torch.Tensor,
+                            scale: float = 0.0, stream=None) -> None:
+    """l2kv_decode_attn over the library's own scratch array (no workspace argument)."""
+    _dev(Q, Kc, Vc, O)
+    B, Hq, D = Q.shape
+    Bk, Hkv, n, Dk = Kc.shape
+    assert (Bk, Dk) == (B, D) and Vc.shape == Kc.shape and Kc.dtype == Q.dtype == Vc.dtype
+    assert O.dtype == torch.float32 and O.numel() == B * Hq * D
+    _check("l2kv_decode_attn_static", lib().l2kv_decode_attn_static(
+        _ptr(Q), _ptr(Kc), _ptr(Vc), _dtype_code(Q), B, Hq, Hkv, n, D, n * D, float(scale), _ptr(O),
+        _stream(stream)))
 
 
 # ------------------------------------------------- ragged batches / streaming

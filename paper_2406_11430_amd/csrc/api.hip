@@ -136,10 +136,10 @@ size_t l2kv_decode_workspace_bytes(int32_t B, int32_t Hq, int64_t kv_len, int32_
     return (raw + 255) / 256 * 256;
 }
 
-l2kv_status l2kv_decode_attn_splits(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt,
-                                    int32_t B, int32_t Hq, int32_t Hkv, int64_t kv_len, int32_t D,
-                                    int64_t kv_head_stride, float scale, int32_t n_splits, float* O,
-                                    void* workspace, size_t workspace_bytes, void* stream) {
+// Argument checks shared by the uniform decode entry points (everything but the workspace).
+static l2kv_status check_decode(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt, int32_t B,
+                                int32_t Hq, int32_t Hkv, int64_t kv_len, int32_t D, int64_t kv_head_stride,
+                                float scale, int32_t n_splits, const float* O) {
     if (Q == nullptr || Kc == nullptr || Vc == nullptr || O == nullptr) return L2KV_ERR_NULL;
     if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || kv_len <= 0 || kv_len > kMaxTokens || !dim_ok(D))
@@ -150,15 +150,47 @@ l2kv_status l2kv_decode_attn_splits(const void* Q, const void* Kc, const void* V
     if (kv_head_stride < kv_len * static_cast<int64_t>(D)) return L2KV_ERR_SHAPE;
     if (n_splits < 0 || n_splits > decode_max_splits(kv_len)) return L2KV_ERR_SHAPE;
     if (!std::isfinite(scale)) return L2KV_ERR_SHAPE;
+    if ((kv_head_stride * elem_bytes(dt)) % 16 != 0) return L2KV_ERR_ALIGN;
+    if (!aligned(Q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(O, 4)) return L2KV_ERR_ALIGN;
+    return L2KV_OK;
+}
+
+l2kv_status l2kv_decode_attn_splits(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt,
+                                    int32_t B, int32_t Hq, int32_t Hkv, int64_t kv_len, int32_t D,
+                                    int64_t kv_head_stride, float scale, int32_t n_splits, float* O,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+    l2kv_status st = check_decode(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, scale, n_splits, O);
+    // the workspace is checked in the place it always had among the checks: after the sizes,
+    // before the alignments
+    if (st != L2KV_OK && st != L2KV_ERR_ALIGN) return st;
     if (workspace == nullptr || workspace_bytes < l2kv_decode_workspace_bytes(B, Hq, kv_len, D))
         return L2KV_ERR_WORKSPACE;
-    if ((kv_head_stride * elem_bytes(dt)) % 16 != 0) return L2KV_ERR_ALIGN;
-    if (!aligned(Q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(O, 4) || !aligned(workspace, 16))
-        return L2KV_ERR_ALIGN;
+    if (st != L2KV_OK) return st;
+    if (!aligned(workspace, 16)) return L2KV_ERR_ALIGN;
     const float s = scale > 0.f ? scale : 1.0f / std::sqrt(static_cast<float>(D));
     const DecodePlan plan = decode_plan(B, Hkv, Hq / Hkv, kv_len, n_splits);
     return decode_dispatch(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, nullptr, nullptr, nullptr, s,
                            plan, O, workspace, static_cast<hipStream_t>(stream));
+}
+
+l2kv_status l2kv_decode_attn_static(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt,
+                                    int32_t B, int32_t Hq, int32_t Hkv, int64_t kv_len, int32_t D,
+                                    int64_t kv_head_stride, float scale, float* O, void* stream) {
+    if (l2kv_status st = check_decode(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, scale, 0, O);
+        st != L2KV_OK)
+        return st;
+    const float s = scale > 0.f ? scale : 1.0f / std::sqrt(static_cast<float>(D));
+    const DecodePlan plan = decode_plan(B, Hkv, Hq / Hkv, kv_len, 0);
+    // counters + the partials of the workgroups this launch really has
+    const size_t need = decode_counter_bytes(B, Hkv) +
+                        static_cast<size_t>(B) * static_cast<size_t>(Hq) * static_cast<size_t>(plan.n_splits) *
+                            static_cast<size_t>(D + 2) * sizeof(float);
+    if (need > static_cast<size_t>(L2KV_STATIC_SCRATCH_BYTES)) return L2KV_ERR_WORKSPACE;
+    l2kv_status st = L2KV_OK;
+    void* scratch_ptr = decode_static_scratch(static_cast<hipStream_t>(stream), &st);
+    if (scratch_ptr == nullptr) return st;
+    return decode_dispatch(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, nullptr, nullptr, nullptr, s,
+                           plan, O, scratch_ptr, static_cast<hipStream_t>(stream));
 }
 
 l2kv_status l2kv_decode_attn(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt, int32_t B,
@@ -379,6 +411,6 @@ const char* l2kv_status_string(l2kv_status s) {
     return "unknown status";
 }
 
-int32_t l2kv_version(void) { return 200; }
+int32_t l2kv_version(void) { return 300; }
 
 }  // extern "C"

@@ -452,6 +452,44 @@ l2kv_status workspace_init_dispatch(void* workspace, size_t bytes, hipStream_t s
     return launch_status();
 }
 
+// ---- scratch memory of the allocation-free entry point ----------------------
+// Callers that cannot allocate (graph capture, serving loops, harnesses that
+// forbid hipMalloc) get the decode workspace from this array instead of from an
+// argument.  Every device the library runs on holds its own copy at its own
+// address.  On the host the array's name is only a handle for the symbol
+// look-up below, never a device address: host code uses the pointer that
+// hipGetSymbolAddress returned for the current device, and nothing else.
+static __device__ __align__(256) unsigned char scratch[L2KV_STATIC_SCRATCH_BYTES];
+
+void* decode_static_scratch(hipStream_t stream, l2kv_status* status) {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void*> device_ptr[kMaxDevices];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        *status = L2KV_ERR_LAUNCH;
+        return nullptr;
+    }
+    void* ptr = device_ptr[dev].load(std::memory_order_acquire);
+    if (ptr != nullptr) return ptr;
+    // First use on this device (which is current): look the array's address up and
+    // zero the arrival counters at its start with the fill kernel.  Every later
+    // call finds them zero because every decode launch resets the counters it used.
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+        (void)hipGetLastError();
+        *status = L2KV_ERR_LAUNCH;
+        return nullptr;
+    }
+    constexpr size_t kCounterRegion = 65536 * sizeof(uint32_t);      // B * Hkv <= 65535 counters
+    static_assert(kCounterRegion <= L2KV_STATIC_SCRATCH_BYTES, "scratch smaller than its counter region");
+    if (l2kv_status st = workspace_init_dispatch(ptr, kCounterRegion, stream); st != L2KV_OK) {
+        *status = st;
+        return nullptr;
+    }
+    device_ptr[dev].store(ptr, std::memory_order_release);
+    return ptr;
+}
+
 int32_t decode_max_splits(int64_t kv_len) {
     if (kv_len <= 0) return 0;
     const int64_t by_rows = (kv_len + kDecodeRowTile - 1) / kDecodeRowTile;

@@ -46,6 +46,9 @@ inline size_t decode_counter_bytes(int32_t B, int32_t Hkv) {
     return (raw + 255) / 256 * 256;
 }
 l2kv_status workspace_init_dispatch(void* workspace, size_t bytes, hipStream_t stream);
+// Device address of the library's own scratch array on the current device (set up on first use,
+// which enqueues one fill kernel on `stream`); nullptr with *status set on failure.
+void* decode_static_scratch(hipStream_t stream, l2kv_status* status);
 DecodePlan decode_plan(int32_t B, int32_t Hkv, int32_t group, int64_t kv_len, int32_t requested_splits);
 DecodePlan decode_plan_ragged(int32_t n_seq, int32_t Hkv, int64_t max_len, int32_t requested_splits,
                               bool ordered);

@@ -152,6 +152,29 @@ def test_decode_validation(lib):
     assert g(P, P, P, 1, 2, 8, 2, 100, 128, 12800, 0.0, -1, P, P, ws, None) == E_SHAPE
 
 
+def test_decode_static_validation(lib):
+    f = lib.l2kv_decode_attn_static
+    ok = (P, P, P, 1, 2, 8, 2, 100, 128, 12800, 0.0, P, None)
+    names = ["Q", "Kc", "Vc", "dt", "B", "Hq", "Hkv", "kv_len", "D", "stride", "scale", "O", "stream"]
+
+    def call(**kw):
+        args = list(ok)
+        for key, val in kw.items():
+            args[names.index(key)] = val
+        return f(*args)
+
+    for key in ("Q", "Kc", "Vc", "O"):
+        assert call(**{key: None}) == E_NULL
+    assert call(dt=5) == E_DTYPE
+    assert call(B=0) == E_SHAPE and call(Hq=18) == E_SHAPE and call(D=80) == E_SHAPE and call(kv_len=0) == E_SHAPE
+    assert call(stride=100 * 128 - 1) == E_SHAPE and call(scale=float("inf")) == E_SHAPE
+    assert call(Q=P + 4) == E_ALIGN and call(O=P + 2) == E_ALIGN
+    # beyond the scratch array: 4096 sequences x 8 heads x 130 floats of partials alone exceed 4 MiB
+    assert call(B=4096, Hq=8, Hkv=8, kv_len=64, stride=64 * 128) == E_WS
+    header = open(HEADER).read()
+    assert re.search(r"#define\s+L2KV_STATIC_SCRATCH_BYTES\s+\(4u << 20\)", header)
+
+
 def test_workspace_init_and_random_keys_validation(lib):
     f = lib.l2kv_decode_workspace_init
     assert f(None, 256, None) == E_NULL

@@ -517,6 +517,507 @@ def test_random_keys_hash_known_values_and_spread():
     assert counts.sum() == 2048 and counts.min() > 430 and counts.max() < 600
 
 
+def _undo_xorshift(y, s):
+    """Solve y = x ^ (x >> s) for x on 32 bits: the top s bits of x are those of y, every further
+    block of s bits follows from the block above it."""
+    x = y
+    for _ in range(32 // s + 1):
+        x = y ^ (x >> s)
+    return x
+
+
+def test_random_keys_inverted_back_to_head_and_token():
+    # The hash is a bijection on 32-bit words, so it is pinned by its INVERSE, which shares no step
+    # with the forward formula: xor-shifts are undone block by block, the odd multipliers by their
+    # modular inverses (computed by Python's pow, not typed in), the counter by subtracting the seed
+    # and head terms and dividing by the odd token multiplier.  A changed shift or constant in the
+    # oracle does not come back to (head, token).
+    M = 1 << 32
+    inv_c1, inv_c2, inv_tok = pow(0x85EBCA6B, -1, M), pow(0xC2B2AE35, -1, M), pow(0x9E3779B1, -1, M)
+    assert (inv_c1 * 0x85EBCA6B) % M == 1 and (inv_c2 * 0xC2B2AE35) % M == 1 and (inv_tok * 0x9E3779B1) % M == 1
+    seed, n_heads, T = 0xC0FFEE11, 3, 5000
+    keys = oracle.random_keys(n_heads, T, seed).view(np.uint32)
+    for h in range(n_heads):
+        for t in range(T):
+            x = _undo_xorshift(int(keys[h, t]), 16)
+            x = (x * inv_c2) % M
+            x = _undo_xorshift(x, 13)
+            x = (x * inv_c1) % M
+            x = _undo_xorshift(x, 16)
+            assert ((x - seed - h * 0x85EBCA77) * inv_tok) % M == t, (h, t)
+    # the finalizer's value at 1, as quoted wherever the MurmurHash3 32-bit finalizer is tabulated
+    # (seed 1, head 0, token 0 make its input 1)
+    assert int(oracle.random_keys(1, 1, 1).view(np.uint32)[0, 0]) == 0x514E28B7
+
+
+def test_random_keys_avalanche():
+    # a finalizer of this kind flips about half of the 32 output bits when ONE input bit flips;
+    # with a missing or misplaced mixing step some input bits reach only a few output bits.
+    # For head 0 and token 0 the hash input is the seed itself, so flipping bit b of the seed
+    # flips exactly bit b of the input word.
+    rng = np.random.default_rng(5)
+    Ki = rng.integers(-8, 9, size=(3, 37, D))
+    K = Ki.astype(np.float32)
+    Kin = bf16_bits(K) if dt == "bf16" else K
+    n32, n64 = oracle.norms(Kin, dt)
+    want = (Ki.astype(np.int64) ** 2).sum(-1)
+    assert np.array_equal(n32.astype(np.int64), want)
+    assert np.array_equal(n64, want.astype(np.float64))
+
+
+@pytest.mark.parametrize("dt,D", [("f32", 64), ("bf16", 128)])
+def test_norm_close_to_fp64_and_numpy(dt, D):
+    rng = np.random.default_rng(11)
+    K = (rng.standard_normal((2, 2, 100, D)) *
+         np.exp(0.5 * rng.standard_normal((2, 2, 100, 1)))).astype(np.float32)
+    if dt == "bf16":
+        Kin = bf16_bits(K)
+        Kd = bf16_to_f64(Kin)
+    else:
+        Kin, Kd = K, K.astype(np.float64)
+    n32, n64 = oracle.norms(Kin, dt)
+    truth = (Kd ** 2).sum(-1)
+    assert n32.shape == truth.shape
+    np.testing.assert_allclose(n64, truth, rtol=1e-14)
+    # fp32 tree sum: error bounded by (depth+1) half-ulps of the result
+    np.testing.assert_allclose(n32, truth, rtol=(D // 16 + 5) * 2.0 ** -24)
+
+
+def test_norm_single_coordinate_closed_form():
+    # K_t = c_t e_{t mod D}: squared norm is c_t^2 (one rounding for fp32).
+    D, T = 64, 130
+    c = np.linspace(0.1, 9.0, T).astype(np.float32)
+    K = np.zeros((1, T, D), dtype=np.float32)
+    K[0, np.arange(T), np.arange(T) % D] = c
+    n32, _ = oracle.norms(K, "f32")
+    assert np.array_equal(n32[0], (c * c).astype(np.float32))
+
+
+def test_norm_power_of_two_scaling_is_exact():
+    rng = np.random.default_rng(3)
+    K = rng.standard_normal((1, 50, 128)).astype(np.float32)
+    a, _ = oracle.norms(K, "f32")
+    b, _ = oracle.norms(K * np.float32(4.0), "f32")
+    assert np.array_equal(b, a * np.float32(16.0))
+
+
+# ---------------------------------------------------------------- selection
+@pytest.mark.parametrize("seed", range(6))
+def test_select_matches_brute_force_rank_counting(seed):
+    rng = np.random.default_rng(seed)
+    T = int(rng.integers(1, 65))
+    # few distinct values -> many ties
+    vals = rng.choice(np.array([0.0, 0.25, 1.0, 1.5, 7.0, np.inf], dtype=np.float32), size=T)
+    if seed % 2:
+        vals = rng.random(T).astype(np.float32)
+    for k in sorted({1, T, max(1, T // 2), max(1, T // 3)}):
+        got = oracle.select(vals[None, :], k)[0]
+        assert np.array_equal(got, brute_force_kept(vals, k))
+
+
+def test_select_all_equal_norms_is_pure_tiebreak():
+    n = np.full((2, 33), 3.5, dtype=np.float32)
+    assert np.array_equal(oracle.select(n, 10), np.tile(np.arange(10, dtype=np.int32), (2, 1)))
+    # highest-norm mode breaks ties the same way
+    assert np.array_equal(oracle.select(n, 10, oracle.MODE_HIGHEST),
+                          np.tile(np.arange(10, dtype=np.int32), (2, 1)))
+
+
+def test_select_matches_stable_argsort_and_topk():
+    rng = np.random.default_rng(42)
+    n = rng.random((5, 777)).astype(np.float32)
+    n[:, ::7] = n[:, 3:4]                       # inject ties
+    k = 300
+    got = oracle.select(n, k)
+    for h in range(n.shape[0]):
+        want = np.sort(np.argsort(n[h], kind="stable")[:k]).astype(np.int32)
+        assert np.array_equal(got[h], want)
+    # torch.topk agrees on the VALUES kept (tie order is its own business)
+    tv = torch.topk(torch.from_numpy(n), k, dim=1, largest=False).values.sort(dim=1).values.numpy()
+    gv = np.sort(np.take_along_axis(n, got, axis=1), axis=1)
+    assert np.array_equal(tv, gv)
+
+
+def test_select_invariants():
+    rng = np.random.default_rng(8)
+    T = 500
+    n = np.exp(rng.standard_normal((4, T))).astype(np.float32)
+    bits = n.view(np.uint32).astype(np.int64)
+    prev = None
+    for r in (0.1, 0.37, 0.5, 0.9, 1.0):
+        k = oracle.keep_count(T, r)
+        idx = oracle.select(n, k)
+        assert idx.shape == (4, k)
+        for h in range(4):
+            kept = idx[h]
+            assert np.all(np.diff(kept) > 0)               # strictly ascending
+            mask = np.zeros(T, bool)
+            mask[kept] = True
+            if k < T:                                      # threshold property
+                key = bits[h] * T + np.arange(T)
+                assert key[mask].max() < key[~mask].min()
+        if prev is not None:                               # nesting
+            for h in range(4):
+                assert set(prev[h]).issubset(set(idx[h]))
+        prev = idx
+    assert np.array_equal(oracle.select(n, T), np.tile(np.arange(T, dtype=np.int32), (4, 1)))
+
+
+def test_select_token_permutation_equivariance_and_pow2_scale():
+    rng = np.random.default_rng(9)
+    T, k = 301, 77
+    n = rng.random((1, T)).astype(np.float32)          # distinct with prob. 1
+    assert len(np.unique(n)) == T
+    base = set(oracle.select(n, k)[0])
+    perm = rng.permutation(T)
+    n_perm = n[:, perm]                                # new position j holds old perm[j]
+    got = oracle.select(n_perm, k)[0]
+    assert {int(perm[j]) for j in got} == base
+    assert set(oracle.select(n * np.float32(0.25), k)[0]) == base
+
+
+def test_select_highest_is_complement_of_lowest_when_distinct():
+    rng = np.random.default_rng(10)
+    T, k = 200, 60
+    n = rng.random((3, T)).astype(np.float32)
+    hi = oracle.select(n, k, oracle.MODE_HIGHEST)
+    lo = oracle.select(n, T - k, oracle.MODE_LOWEST)
+    for h in range(3):
+        assert set(hi[h]) | set(lo[h]) == set(range(T))
+        assert not (set(hi[h]) & set(lo[h]))
+
+
+def test_select_inf_and_nan_patterns_evicted_first():
+    n = np.array([[1.0, np.inf, 0.5, np.nan, 2.0, 0.0]], dtype=np.float32)
+    assert list(oracle.select(n, 4)[0]) == [0, 2, 4, 5]
+    assert list(oracle.select(n, 5)[0]) == [0, 1, 2, 4, 5]   # inf before nan
+
+
+# --------------------------------------------------------------- compaction
+def test_compact_is_a_row_gather():
+    rng = np.random.default_rng(1)
+    X = rng.integers(0, 65536, size=(2, 3, 50, 128)).astype(np.uint16)
+    idx = np.sort(rng.permuted(np.tile(np.arange(50), (2, 3, 1)), axis=-1)[..., :20], axis=-1).astype(np.int32)
+    got = oracle.compact(X, idx)
+    want = np.take_along_axis(X, idx[..., None].astype(np.int64), axis=2)
+    assert got.dtype == X.dtype and np.array_equal(got, want)
+    with pytest.raises(IndexError):
+        oracle.compact(X, np.full((2, 3, 1), 50, dtype=np.int32))
+
+
+# ---------------------------------------------------------------- attention
+def _rand_case(rng, B, Hq, Hkv, n, D, dt):
+    Q = rng.standard_normal((B, Hq, D)).astype(np.float32)
+    K = rng.standard_normal((B, Hkv, n, D)).astype(np.float32)
+    V = rng.standard_normal((B, Hkv, n, D)).astype(np.float32)
+    if dt == "bf16":
+        return bf16_bits(Q), bf16_bits(K), bf16_bits(V)
+    return Q, K, V
+
+
+def _as_f64(x, dt):
+    return bf16_to_f64(x) if dt == "bf16" else x.astype(np.float64)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("B,Hq,Hkv,n,D", [(2, 8, 2, 37, 64), (1, 4, 4, 5, 128), (3, 6, 3, 64, 16)])
+def test_attention_matches_numpy_and_torch_fp64(dt, B, Hq, Hkv, n, D):
+    rng = np.random.default_rng(B * 100 + n)
+    Q, K, V = _rand_case(rng, B, Hq, Hkv, n, D, dt)
+    got = oracle.decode_attn(Q, K, V, dt)
+    q, k, v = _as_f64(Q, dt), _as_f64(K, dt), _as_f64(V, dt)
+    G = Hq // Hkv
+    # explicit repeat: query head hq uses KV head hq // G
+    kk = np.repeat(k, G, axis=1)
+    vv = np.repeat(v, G, axis=1)
+    s = np.einsum("bhd,bhnd->bhn", q, kk) / np.sqrt(D)
+    p = np.exp(s - s.max(-1, keepdims=True))
+    p /= p.sum(-1, keepdims=True)
+    want = np.einsum("bhn,bhnd->bhd", p, vv)
+    np.testing.assert_allclose(got, want, rtol=0, atol=2e-7 * max(1.0, np.abs(want).max()))
+    # library routine: torch scaled_dot_product_attention in fp64 on the CPU
+    t = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q)[:, :, None, :], torch.from_numpy(kk), torch.from_numpy(vv))
+    np.testing.assert_allclose(got, t[:, :, 0, :].numpy(), rtol=0,
+                               atol=2e-7 * max(1.0, np.abs(want).max()))
+
+
+def test_attention_gqa_mapping_is_consecutive_groups():
+    # KV head j holds V rows all equal to j: output of query head hq must be hq // G.
+    B, Hq, Hkv, n, D = 1, 8, 2, 9, 64
+    rng = np.random.default_rng(2)
+    Q = rng.standard_normal((B, Hq, D)).astype(np.float32)
+    K = rng.standard_normal((B, Hkv, n, D)).astype(np.float32)
+    V = np.zeros((B, Hkv, n, D), dtype=np.float32)
+    V[0, 1] = 1.0
+    got = oracle.decode_attn(Q, K, V, "f32")
+    want = (np.arange(Hq) // (Hq // Hkv)).astype(np.float32)
+    np.testing.assert_allclose(got[0, :, 0], want, atol=1e-7)
+    np.testing.assert_allclose(got[0], np.repeat(want[:, None], D, 1), atol=1e-7)
+
+
+def test_attention_closed_forms():
+    rng = np.random.default_rng(4)
+    B, Hq, Hkv, n, D = 2, 4, 2, 23, 64
+    Q, K, V = _rand_case(rng, B, Hq, Hkv, n, D, "f32")
+    # (1) zero keys or zero query -> plain mean of the value rows
+    mean_v = np.repeat(V.astype(np.float64).mean(2), Hq // Hkv, axis=1)
+    np.testing.assert_allclose(oracle.decode_attn(Q, np.zeros_like(K), V, "f32"), mean_v, atol=1e-6)
+    np.testing.assert_allclose(oracle.decode_attn(np.zeros_like(Q), K, V, "f32"), mean_v, atol=1e-6)
+    # (2) all value rows equal -> that row
+    v0 = rng.standard_normal(D).astype(np.float32)
+    Vc = np.broadcast_to(v0, V.shape).copy()
+    np.testing.assert_allclose(oracle.decode_attn(Q, K, Vc, "f32"),
+                               np.broadcast_to(v0, (B, Hq, D)), atol=1e-6)
+    # (3) one key aligned with q at a large scale -> its value row
+    K3 = K.copy()
+    for b in range(B):
+        for hkv in range(Hkv):
+            K3[b, hkv, 7] = 50.0 * Q[b, hkv * (Hq // Hkv)]
+    got = oracle.decode_attn(Q, K3, V, "f32")
+    for b in range(B):
+        for hkv in range(Hkv):
+            np.testing.assert_allclose(got[b, hkv * (Hq // Hkv)], V[b, hkv, 7], atol=1e-5)
+    # (4) explicit scale: scale=1/sqrt(D) equals the default; doubling it differs
+    d0 = oracle.decode_attn(Q, K, V, "f32")
+    d1 = oracle.decode_attn(Q, K, V, "f32", scale=1.0 / np.sqrt(D))
+    np.testing.assert_allclose(d0, d1, atol=1e-7)
+    assert np.abs(oracle.decode_attn(Q, K, V, "f32", scale=2.0 / np.sqrt(D)) - d0).max() > 1e-3
+    # (5) a constant added to every logit changes nothing: append a coordinate
+    #     block (constant in K, 1 in q); D grows from 64 to 128, scale held fixed.
+    Kx = np.concatenate([K, np.zeros_like(K)], axis=-1)
+    Kx[..., D] = 3.0
+    Qx = np.concatenate([Q, np.zeros_like(Q)], axis=-1)
+    Qx[..., D] = 1.0
+    Vx = np.concatenate([V, V], axis=-1)
+    dx = oracle.decode_attn(Qx, Kx, Vx, "f32", scale=1.0 / np.sqrt(D))
+    np.testing.assert_allclose(dx[..., :D], d0, atol=1e-6)
+    # (6) permuting the cached rows (K and V together) changes nothing
+    perm = rng.permutation(n)
+    np.testing.assert_allclose(oracle.decode_attn(Q, K[:, :, perm], V[:, :, perm], "f32"), d0, atol=1e-6)
+
+
+def test_attention_two_rows_is_a_sigmoid():
+    # n = 2: weights are sigmoid(+-(s0-s1)); check against math.exp directly.
+    D = 16
+    q = np.zeros((1, 1, D), np.float32)
+    q[0, 0, 0] = 4.0                        # / sqrt(16) -> logit = K[.,0]
+    K = np.zeros((1, 1, 2, D), np.float32)
+    K[0, 0, 0, 0], K[0, 0, 1, 0] = 1.0, -0.5
+    V = np.zeros((1, 1, 2, D), np.float32)
+    V[0, 0, 0, :], V[0, 0, 1, :] = 2.0, -1.0
+    w0 = 1.0 / (1.0 + np.exp(-1.5))
+    got = oracle.decode_attn(q, K, V, "f32")
+    np.testing.assert_allclose(got[0, 0], np.full(D, 2.0 * w0 - 1.0 * (1 - w0)), atol=1e-7)
+
+
+# ------------------------------------------------------------ whole pipeline
+def test_worked_example(golden_dir):
+    g = parse_golden(os.path.join(golden_dir, "worked_example.txt"))
+    T, D = 8, 16
+    c = np.array(g["c"], dtype=np.float32)
+    w = np.array(g["w"], dtype=np.float64)
+    K = np.zeros((1, 1, T, D), np.float32)
+    K[0, 0, np.arange(T), np.arange(T)] = c
+    V = np.zeros((1, 1, T, D), np.float32)
+    for t in range(T):
+        V[0, 0, t, :] = t + 1
+        V[0, 0, t, t] += 10
+    Q = np.zeros((1, 1, D), np.float32)
+    Q[0, 0, :T] = (4.0 * np.log(w) / c.astype(np.float64)).astype(np.float32)
+
+    n32, n64 = oracle.norms(K, "f32")
+    assert np.array_equal(n32[0, 0], np.array(g["norm2"], np.float32))
+    for r, key in ((0.5, "kept_r0.5"), (0.25, "kept_r0.25"), (0.3, "kept_r0.3")):
+        k = oracle.keep_count(T, r)
+        assert k == len(g[key])
+        assert list(oracle.select(n32, k)[0, 0]) == [int(v) for v in g[key]]
+    assert list(oracle.select(n32, 3, oracle.MODE_HIGHEST)[0, 0]) == [int(v) for v in g["kept_high_3"]]
+
+    _, _, idx, Kc, Vc = oracle.compress(K, V, "f32", 0.5)
+    assert np.array_equal(Kc[0, 0], K[0, 0, idx[0, 0]])
+    assert np.array_equal(Vc[0, 0], V[0, 0, idx[0, 0]])
+    out = oracle.decode_attn(Q, Kc, Vc, "f32")
+    np.testing.assert_allclose(out[0, 0], np.array(g["out_r0.5"]), atol=2e-6)
+    _, _, idx1, Kc1, Vc1 = oracle.compress(K, V, "f32", 1.0)
+    assert np.array_equal(idx1[0, 0], np.arange(T))
+    assert np.array_equal(Kc1, K) and np.array_equal(Vc1, V)
+    out1 = oracle.decode_attn(Q, Kc1, Vc1, "f32")
+    np.testing.assert_allclose(out1[0, 0], np.array(g["out_r1.0"]), atol=2e-6)
+
+
+def test_kept_set_ignores_values_and_queries_and_keep1_is_full_attention():
+    from paper_2406_11430_amd import synth
+    cfg = synth.CONFIGS["C1"].scaled(T=96)
+    K, V = synth.make_layer(cfg, 0)
+    Kn, Vn = synth.as_numpy_bits(K), synth.as_numpy_bits(V)
+    _, _, idx, Kc, Vc = oracle.compress(Kn, Vn, "f32", 0.5)
+    assert idx.shape[-1] == 48
+    rng = np.random.default_rng(0)
+    V2 = rng.permuted(Vn, axis=2)
+    _, _, idx2, _, _ = oracle.compress(Kn, V2, "f32", 0.5)
+    assert np.array_equal(idx, idx2)
+    # sinks (first four tokens, keys scaled by 0.1) survive in every head
+    assert np.all(idx[..., :4] == np.arange(4))
+    Q = synth.as_numpy_bits(synth.make_query(cfg, 0, 0))
+    _, _, _, K1, V1 = oracle.compress(Kn, Vn, "f32", 1.0)
+    np.testing.assert_array_equal(oracle.decode_attn(Q, K1, V1, "f32"),
+                                  oracle.decode_attn(Q, Kn, Vn, "f32"))
+
+
+# ------------------------------------------------------------ streaming eviction
+def _stream_tokens(rng, T, D, dt, ties=False):
+    K = rng.standard_normal((T, D)).astype(np.float32) * np.exp(0.5 * rng.standard_normal((T, 1))).astype(np.float32)
+    if ties:
+        K[::3] = K[0]                                   # many equal norms
+    V = rng.standard_normal((T, D)).astype(np.float32)
+    if dt == "bf16":
+        return bf16_bits(K), bf16_bits(V)
+    return K, V
+
+
+@pytest.mark.parametrize("dt,D", [("f32", 64), ("bf16", 128)])
+@pytest.mark.parametrize("ties", [False, True])
+def test_stream_fixed_budget_equals_one_shot_selection(dt, D, ties):
+    # classic streaming top-k: with a fixed budget the kept token set after every step is the
+    # one-shot selection over all tokens seen so far (lowest (norm bits, id), exact count)
+    rng = np.random.default_rng(5 + D)
+    T, budget = 90, 17
+    K, V = _stream_tokens(rng, T, D, dt, ties)
+    n32, _ = oracle.norms(K[None], dt)
+    head = oracle.StreamHead(budget + 1, D, dt)
+    for t in range(T):
+        head.append(K[t], V[t], t)
+        assert head.evict_to(budget) == (1 if t >= budget else 0)
+        ids, Kk, Vk, nk = head.kept()
+        want = oracle.select(n32[:, : t + 1], min(budget, t + 1))[0]
+        assert np.array_equal(ids, want)
+        assert np.array_equal(Kk, K[want]) and np.array_equal(Vk, V[want])
+        assert np.array_equal(nk.view(np.uint32), n32[0, want].view(np.uint32))
+
+
+def test_stream_eviction_drops_largest_norm_then_largest_id():
+    D = 16
+    head = oracle.StreamHead(8, D, "f32")
+    vals = [2.0, 3.0, 1.0, 3.0, 0.5, 3.0]              # squared norms 4, 9, 1, 9, .25, 9
+    for t, v in enumerate(vals):
+        row = np.zeros(D, np.float32)
+        row[t] = v
+        head.append(row, row, t)
+    assert head.evict_to(5) == 1 and list(head.kept()[0]) == [0, 1, 2, 3, 4]      # id 5 (norm 9, latest) first
+    assert head.evict_to(3) == 2 and list(head.kept()[0]) == [0, 2, 4]            # then ids 3 and 1
+    assert head.evict_to(3) == 0
+    assert head.evict_to(0) == 3 and len(head) == 0
+
+
+def test_stream_growing_budget_and_attention():
+    # budget(t) = keep_count(L0 + t, r): start from a compressed prompt, decode 40 steps
+    rng = np.random.default_rng(77)
+    D, dt, L0, r, steps, G = 64, "f32", 50, 0.5, 40, 2
+    K, V = _stream_tokens(rng, L0 + steps, D, dt)
+    n32, _ = oracle.norms(K[None], dt)
+    k0 = oracle.keep_count(L0, r)
+    idx0 = oracle.select(n32[:, :L0], k0)[0]
+    cap = oracle.keep_count(L0 + steps, r) + 1
+    head = oracle.StreamHead(cap, D, dt)
+    head.load(K[idx0], V[idx0], n32[0, idx0], idx0.astype(np.int32))
+    for t in range(steps):
+        tok = L0 + t
+        head.append(K[tok], V[tok], tok)
+        q = rng.standard_normal((G, D)).astype(np.float32)
+        out = head.attend(q)
+        ids = head.kept()[0]
+        # attention over the slots equals attention over the same tokens in any order
+        want = oracle.decode_attn(q[None], K[None, None, ids], V[None, None, ids], dt)[0]
+        np.testing.assert_allclose(out, want, atol=1e-6)
+        head.evict_to(oracle.keep_count(tok + 1, r))
+        assert len(head) == oracle.keep_count(tok + 1, r)
+        # evicting is monotone: a token once dropped never comes back, the newest may be dropped at once
+        assert set(head.kept()[0]) <= set(ids)
+
+
+# ------------------------------------------------------------ keep-random control
+def test_random_keys_hash_known_values_and_spread():
+    # hand-evaluated values of the stated hash (token*0x9E3779B1 + head*0x85EBCA77 + seed, then the
+    # MurmurHash3 32-bit finalizer), computed here with Python integers
+    def ref(seed, h, t):
+        x = (t * 0x9E3779B1 + h * 0x85EBCA77 + seed) & 0xFFFFFFFF
+        x ^= x >> 16
+        x = (x * 0x85EBCA6B) & 0xFFFFFFFF
+        x ^= x >> 13
+        x = (x * 0xC2B2AE35) & 0xFFFFFFFF
+        x ^= x >> 16
+        return x
+    keys = oracle.random_keys(3, 50, 12345).view(np.uint32)
+    for h in range(3):
+        for t in (0, 1, 7, 49):
+            assert int(keys[h, t]) == ref(12345, h, t)
+    assert ref(0, 0, 0) == 0                               # the finalizer maps 0 to 0
+    # a bijection of the counter: distinct inside a head, different between heads and seeds
+    big = oracle.random_keys(2, 4096, 7).view(np.uint32)
+    assert len(np.unique(big[0])) == 4096 and not np.array_equal(big[0], big[1])
+    assert not np.array_equal(oracle.random_keys(1, 64, 1), oracle.random_keys(1, 64, 2))
+    # the kept set is spread evenly over the sequence (each quarter holds about a quarter)
+    kept = oracle.select(oracle.random_keys(1, 4096, 99), 2048)[0]
+    counts = np.histogram(kept, bins=4, range=(0, 4096))[0]
+    assert counts.sum() == 2048 and counts.min() > 430 and counts.max() < 600
+
+
+def _undo_xorshift(y, s):
+    """Solve y = x ^ (x >> s) for x on 32 bits: the top s bits of x are those of y, every further
+    block of s bits follows from the block above it."""
+    x = y
+    for _ in range(32 // s + 1):
+        x = y ^ (x >> s)
+    return x
+
+
+def test_random_keys_inverted_back_to_head_and_token():
+    # The hash is a bijection on 32-bit words, so it is pinned by its INVERSE, which shares no step
+    # with the forward formula: xor-shifts are undone block by block, the odd multipliers by their
+    # modular inverses (computed by Python's pow, not typed in), the counter by subtracting the seed
+    # and head terms and dividing by the odd token multiplier.  A changed shift or constant in the
+    # oracle does not come back to (head, token).
+    M = 1 << 32
+    inv_c1, inv_c2, inv_tok = pow(0x85EBCA6B, -1, M), pow(0xC2B2AE35, -1, M), pow(0x9E3779B1, -1, M)
+    assert (inv_c1 * 0x85EBCA6B) % M == 1 and (inv_c2 * 0xC2B2AE35) % M == 1 and (inv_tok * 0x9E3779B1) % M == 1
+    seed, n_heads, T = 0xC0FFEE11, 3, 5000
+    keys = oracle.random_keys(n_heads, T, seed).view(np.uint32)
+    for h in range(n_heads):
+        for t in range(T):
+            x = _undo_xorshift(int(keys[h, t]), 16)
+            x = (x * inv_c2) % M
+            x = _undo_xorshift(x, 13)
+            x = (x * inv_c1) % M
+            x = _undo_xorshift(x, 16)
+            assert ((x - seed - h * 0x85EBCA77) * inv_tok) % M == t, (h, t)
+    # the finalizer's value at 1, as quoted wherever the MurmurHash3 32-bit finalizer is tabulated
+    # (seed 1, head 0, token 0 make its input 1)
+    assert int(oracle.random_keys(1, 1, 1).view(np.uint32)[0, 0]) == 0x514E28B7
+
+
+def test_random_keys_avalanche():
+    # a finalizer of this kind flips about half of the 32 output bits when ONE input bit flips;
+    # with a missing or misplaced mixing step some input bits reach only a few output bits.
+    # Tokens t and t ^ 2^b differ by +-2^b * 0x9E3779B1 in the hash input, so this test drives the
+    # input through the seed instead, which enters the sum unscaled: seed ^ 2^b flips exactly... not
+    # exactly one input bit (a carry may ripple), so flip the bit by adding or subtracting 2^b as the
+    # bit is clear or set -- that IS a single-bit flip of the input word when no carry leaves bit b.
+    rng = np.random.default_rng(5)
+    seeds = rng.integers(0, 1 << 32, 400, dtype=np.uint64)
+    flips = np.zeros(32)
+    for b in range(32):
+        total = 0
+        for s in seeds:
+            s = int(s)
+            a = int(oracle.random_keys(1, 1, s).view(np.uint32)[0, 0])          # input word = s
+            c = int(oracle.random_keys(1, 1, s ^ (1 << b)).view(np.uint32)[0, 0])  # input word = s with bit b flipped
+            total += bin(a ^ c).count("1")
+        flips[b] = total / len(seeds)
+    assert flips.min() >= 10.0 and flips.max() <= 22.0, flips
+    assert abs(flips.mean() - 16.0) < 1.0
+
+
 def test_length_order_is_longest_first_with_index_tiebreak():
     rng = np.random.default_rng(12)
     lens = rng.integers(0, 6, 40)

@@ -54,7 +54,7 @@ typedef enum {
 } l2kv_status;
 
 /* Eviction strategy.  LOWEST is the paper's method; HIGHEST is the control of
- * Sec. 4 ("keeping tokens with highest L2 norm"). */
+ * Sec. 4 (the highest-norm tokens are the ones kept). */
 typedef enum { L2KV_KEEP_LOWEST = 0, L2KV_KEEP_HIGHEST = 1 } l2kv_mode;
 
 /*
@@ -83,8 +83,8 @@ l2kv_status l2kv_norms(const void* K, l2kv_dtype dt, int64_t n_heads, int64_t T,
                        int32_t D, int64_t head_stride, float* norms, void* stream);
 
 /*
- * Selection (Sec. 1: "keeping in memory only the keys with lowest L2 norm";
- * Eq. 5: exactly m pairs dropped per layer and head).  For every head, the
+ * Selection (the eviction rule of Sec. 1: the lowest-norm keys stay in the
+ * cache; Eq. 5: exactly m pairs dropped per layer and head).  For every head, the
  * k = l2kv_keep_count(T, keep_ratio) positions that come first in the total
  * order (uint32 bit pattern of the fp32 squared norm, token index) -- ties go
  * to the lower token index -- written in ascending token order.
@@ -109,7 +109,8 @@ l2kv_status l2kv_select_k(const float* norms, int64_t n_heads, int64_t T,
 size_t l2kv_select_workspace_bytes(int64_t n_heads, int64_t T);
 
 /*
- * Keys for the keep-random control of Sec. 4 ("keeping random tokens"):
+ * Keys for the keep-random control of Sec. 4 (a random subset of the tokens
+ * is kept):
  * keys[i][t] receives, as a 32-bit pattern stored in an fp32 array, the hash
  *     x = t*0x9E3779B1 + i*0x85EBCA77 + seed   (mod 2^32)
  *     x ^= x>>16; x *= 0x85EBCA6B; x ^= x>>13; x *= 0xC2B2AE35; x ^= x>>16
@@ -120,7 +121,7 @@ size_t l2kv_select_workspace_bytes(int64_t n_heads, int64_t T);
 l2kv_status l2kv_random_keys(int64_t n_heads, int64_t T, uint32_t seed, float* keys, void* stream);
 
 /*
- * Compaction ("...and the corresponding values", Sec. 1): the kept rows of K
+ * Compaction (Sec. 1: the values of the kept keys stay with them): the kept rows of K
  * and of V copied, byte for byte and in the order of kept_idx, into dense
  * caches:
  *     Kc[i][j][:] = K[i][kept_idx[i][j]][:],   Vc likewise.

@@ -10,7 +10,7 @@ Functions, each following the passage named in the C source:
 * ``keep_count(T, r)``            -- kept rows k = ceil(r*T) (Sec. 3, |D| = m exact)
 * ``norms(K, dtype)``             -- squared key norms, fp32 fixed order + fp64
 * ``select(n32, k, mode)``        -- lowest-norm positions (Sec. 1 rule), full sort
-* ``compact(X, idx)``             -- gather of kept rows ("and the corresponding values")
+* ``compact(X, idx)``             -- gather of kept rows (Sec. 1: values stay with their keys)
 * ``decode_attn(Q, Kc, Vc, ...)`` -- single-query softmax attention (Eq. 2 / Eq. 4)
 * ``compress(K, V, dtype, r)``    -- the three compression steps in sequence
 * ``StreamHead``                  -- one (sequence, head) cache under streaming

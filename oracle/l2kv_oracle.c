@@ -330,7 +330,7 @@ int l2kv_oracle_stream_evict(void *K, void *V, float *norms, int32_t *pos, int32
 }
 
 /* ------------------------------------------------------------------------
- * Keep-random control (Sec. 4: "keeping random tokens").  The random order is
+ * Keep-random control of Sec. 4 (a random subset of the tokens is kept).  The random order is
  * a counter-based hash of (seed, head, token) so that it can be reproduced
  * anywhere: x = token*0x9E3779B1 + head*0x85EBCA77 + seed (mod 2^32), followed
  * by the 32-bit finalizer of MurmurHash3 (x ^= x>>16; x *= 0x85EBCA6B;

@@ -1,5 +1,5 @@
-// l2kv_compact: gather of the kept K and V rows into dense caches ("the keys
-// with lowest L2 norm, and the corresponding values", arXiv 2406.11430 Sec. 1).
+// l2kv_compact: gather of the kept K and V rows into dense caches (arXiv
+// 2406.11430 Sec. 1: the lowest-norm keys are kept, each with its value).
 //
 // A byte copy of whole rows: 16 lanes move one row (16 bytes per lane for the
 // 256-byte rows of the supported shapes), a wavefront moves 4 rows per

@@ -276,8 +276,8 @@ static void launch_select_for_length(int64_t longest, const float* norms, int64_
         launch_select<0>(norms, n_heads, T, k, flip, kept_idx, kept_count, stream, rag);
 }
 
-// Keys of the keep-random control (arXiv 2406.11430 Sec. 4, "keeping random
-// tokens"): a counter-based hash of (seed, head, token) written as bit patterns
+// Keys of the keep-random control (arXiv 2406.11430 Sec. 4, where a random
+// subset of the tokens is kept): a counter-based hash of (seed, head, token) written as bit patterns
 // into an fp32 array, on which l2kv_select_k then keeps the k lowest.  The hash
 // is x = token*0x9E3779B1 + head*0x85EBCA77 + seed followed by the 32-bit
 // finalizer of MurmurHash3.

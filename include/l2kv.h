@@ -27,8 +27,10 @@
  *    must be 16-byte aligned and head_stride*sizeof(elem) a multiple of 16;
  *    norms / index / O / workspace pointers 4-byte aligned (workspace 16).
  *  - Outputs must not alias inputs.
- *  - No global mutable state besides a per-device cache of the compute-unit
- *    count; calls are thread-safe.
+ *  - Global state of the library: a per-device cache of the compute-unit
+ *    count and, for l2kv_decode_attn_static only, the per-device address of
+ *    its scratch array.  No call changes a kernel attribute or a device
+ *    setting.  Calls are thread-safe as long as they do not share a workspace.
  */
 #ifndef L2KV_H
 #define L2KV_H
@@ -201,7 +203,7 @@ size_t  l2kv_decode_workspace_bytes(int32_t B, int32_t Hq, int64_t kv_len, int32
  * per GPU, held until the process ends).  The call itself allocates and frees
  * nothing and records no memset.
  *   Limit: counters (4 bytes per (sequence, KV head), padded to 256) plus
- *   B*Hq*(workgroups per KV head)*(D+2)*4 bytes of partials must fit the
+ *   B*Hq*(workgroups per KV head)*(D+4)*4 bytes of partials must fit the
  *   scratch array; larger shapes return L2KV_ERR_WORKSPACE and launch nothing.
  *   (32k-context batch of 4 x 32 query heads: 0.4 MB.)
  *   All calls on one GPU share that GPU's array: two calls that may overlap in
@@ -310,9 +312,11 @@ l2kv_status l2kv_stream_evict(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, in
  * to its lens[s] occupied slots (0 slots give a zero output row).
  *   seq_order: a DEVICE int32 [n_seq] permutation of 0..n_seq-1 giving
  *             the order in which the sequences are launched; with the longest
- *             sequence first (l2kv_length_order) the library uses fewer,
- *             larger workgroups and lets the hardware balance them, which is
- *             faster on batches of mixed lengths.  It only steers scheduling:
+ *             sequence first (l2kv_length_order) the library hands whole
+ *             (sequence, KV head) pairs, longest first, to one workgroup per
+ *             compute unit, whichever is free next (a work list in the
+ *             workspace), which is faster on batches of mixed lengths.  It only
+ *             steers scheduling:
  *             outputs land at the sequence's own rows of O in any case.  An
  *             array that is not a permutation computes some sequences twice
  *             and others not at all (entries are forced into 0..n_seq-1).
@@ -320,10 +324,8 @@ l2kv_status l2kv_stream_evict(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, in
  *             NULL: batches of 2..512 sequences whose longest has 2048 rows or
  *             more get a longest-first order worked out inside the call (one
  *             small extra kernel, about 7 us per call on an MI355X); all other
- *             batches are launched in batch order.
- *             The first ordered call for a (dtype, D, Hq/Hkv) on a device sets a
- *             launch attribute of the kernel and must not be made under graph
- *             capture; later calls are plain launches.
+ *             batches are launched in batch order.  Either way the call is
+ *             made of plain kernel launches and may be captured into a graph.
  *   max_len : an upper bound of all lens[s] (sizes the decomposition and the
  *             workspace; rows beyond it are still attended to)
  *   n_splits: 0 = library default

@@ -17,7 +17,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libl2kv.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "norms.hip", "select.hip", "compact.hip", "decode_attn.hip", "stream.hip", "alr.hip"]
+SOURCES = ["decode_attn_bf16_128.hip", "decode_attn_bf16_64.hip", "decode_attn_f32_128.hip",
+           "decode_attn_f32_64.hip", "api.hip", "norms.hip", "select.hip", "compact.hip", "decode_attn.hip",
+           "stream.hip", "alr.hip"]
 ARCH = "gfx950"
 
 # -packed-fp32-ops is switched off on purpose: the compiler must not form
@@ -50,7 +52,7 @@ def _compile(src: str, extra, obj_dir: str = OBJ_DIR) -> str:
     return obj
 
 
-def build_library(extra_flags=(), jobs: int = 6, out: str = LIB_PATH, obj_dir: str = OBJ_DIR) -> str:
+def build_library(extra_flags=(), jobs: int = 8, out: str = LIB_PATH, obj_dir: str = OBJ_DIR) -> str:
     """Compile every kernel source for gfx950 and link the shared library
     (libl2kv.so in the package unless `out` names another file)."""
     os.makedirs(obj_dir, exist_ok=True)

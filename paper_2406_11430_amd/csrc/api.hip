@@ -131,7 +131,7 @@ size_t l2kv_decode_workspace_bytes(int32_t B, int32_t Hq, int64_t kv_len, int32_
     // counters (at most one per query head: Hkv <= Hq) + split partials
     const size_t raw = decode_counter_bytes(B, Hq) +
                        static_cast<size_t>(B) * static_cast<size_t>(Hq) *
-                           static_cast<size_t>(decode_max_splits(kv_len)) * static_cast<size_t>(D + 2) *
+                           static_cast<size_t>(decode_max_splits(kv_len)) * decode_partial_floats(D) *
                            sizeof(float);
     return (raw + 255) / 256 * 256;
 }
@@ -184,7 +184,7 @@ l2kv_status l2kv_decode_attn_static(const void* Q, const void* Kc, const void* V
     // counters + the partials of the workgroups this launch really has
     const size_t need = decode_counter_bytes(B, Hkv) +
                         static_cast<size_t>(B) * static_cast<size_t>(Hq) * static_cast<size_t>(plan.n_splits) *
-                            static_cast<size_t>(D + 2) * sizeof(float);
+                            decode_partial_floats(D) * sizeof(float);
     if (need > static_cast<size_t>(L2KV_STATIC_SCRATCH_BYTES)) return L2KV_ERR_WORKSPACE;
     l2kv_status st = L2KV_OK;
     void* scratch_ptr = decode_static_scratch(static_cast<hipStream_t>(stream), &st);

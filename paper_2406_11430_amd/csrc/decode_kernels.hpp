@@ -1,0 +1,712 @@
+// l2kv_decode_attn: single-query attention over the compacted cache
+// (arXiv 2406.11430, Eq. 2 in the decode form of Eq. 4).  This is the step the
+// paper's motivation is about: every decode step re-reads the whole cache from
+// HBM, so the kernel is a read stream of Kc and Vc with the arithmetic folded
+// in, and the scores never touch memory.
+//
+// Decomposition: grid (split, sequence x KV head).  The n_splits workgroups of a
+// KV head take turns on consecutive 64-row blocks of its cache and stream them
+// once for all G = Hq/Hkv query heads.  16 lanes share a row (16 bytes each),
+// a wave covers 16 rows of K and of V per step (4 + 4 non-temporal loads per
+// lane) and always has its next tile in flight while it computes on the
+// current one (two register tiles, ping-pong, no branch between a load and its
+// use so the wait counters stay exact).  Every 16-lane row group runs its own
+// online softmax (running max m, denominator l, weighted value sum acc), so the
+// only cross-lane traffic in the loop is the 4-step DPP tree of each dot
+// product.
+//
+// bf16 caches: q.k uses the packed bf16 dot instruction with fp32 accumulate
+// (both operands are exact bf16 inputs); the softmax scale is applied to the
+// fp32 score afterwards.  fp32 caches use plain fp32 FMAs.
+//
+// At the end the 16 row groups of the workgroup are merged through LDS and one
+// partial (acc[D], m, l) per query head goes to the workspace.  The workgroup
+// that finishes last for its KV head (device-scope counter in the workspace)
+// merges the partials of all workgroups and writes O: one kernel per call.
+//
+// Scores are kept in the log2 domain so the exponentials are bare v_exp_f32.
+#pragma once
+#include "l2kv_device.hpp"
+#include "l2kv_host.hpp"
+
+#include <math.h>
+
+
+namespace l2kv {
+
+constexpr int kDecThreads = 256;
+constexpr int kDecWaves = kDecThreads / kWaveSize;                 // 4
+constexpr int kDecLoads = 4;                                        // row loads per lane per step
+constexpr int kDecRowsPerStep = kDecLoads * kRowsPerWaveLoad;       // 16 rows per wave step
+constexpr int kDecGroups = kDecWaves * kRowsPerWaveLoad;            // 16 row groups per workgroup
+static_assert(kDecWaves * kDecRowsPerStep == kDecodeRowTile, "row tile mismatch");
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+
+// K and V are read once per call: streaming loads, nothing to keep in L2.
+template <int W>
+__device__ __forceinline__ Words<W> stream_words(const char* p) { return load_words_stream<W>(p); }
+
+// s_waitcnt immediate for "vmcnt(0)" alone in the gfx9-family encoding that gfx950 uses: vmcnt
+// in bits [3:0] and [15:14] = 0, expcnt [6:4] and lgkmcnt [11:8] left at their maxima.
+constexpr int kWaitVmcnt0 = 0x0F70;
+#if defined(__HIP_DEVICE_COMPILE__) && !defined(__gfx950__)
+#error "the s_waitcnt immediate above is the gfx950 encoding: this file is written for gfx950 only"
+#endif
+
+// Device-scope (agent) relaxed store / load of one float.
+__device__ __forceinline__ void publish(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float fetch(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// 16-byte device-scope load: the same cache policy (sc1) the compiler emits for an
+// agent-scope atomic load of one dword, on a four-dword buffer load.  `region` describes
+// the bytes that may be read (the hardware returns zero outside it).
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+constexpr int kBufferWord3 = 0x00020000;     // raw buffer, 32-bit data format
+constexpr int kCachePolicySc1 = 16;
+__device__ __forceinline__ f32x4 fetch4(__amdgpu_buffer_rsrc_t region, int byte_offset) {
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(region, byte_offset, 0, kCachePolicySc1));
+}
+
+template <typename E, int D>
+struct Tile {
+    Words<Slice<E, D>::kWords> k[kDecLoads];
+    Words<Slice<E, D>::kWords> v[kDecLoads];
+};
+
+// Loads the 16 rows [first_row, first_row+16) of K and V for this lane; all 16
+// rows must exist.  lane_off = rg * row_bytes + c * slice_bytes.
+template <typename E, int D>
+__device__ __forceinline__ void load_tile(Tile<E, D>& t, const char* Kh, const char* Vh,
+                                          int64_t first_row, int lane_off) {
+    using S = Slice<E, D>;
+    const int64_t off = first_row * S::kRowBytes + lane_off;
+#pragma unroll
+    for (int u = 0; u < kDecLoads; ++u)
+        t.k[u] = stream_words<S::kWords>(Kh + off + u * (kRowsPerWaveLoad * S::kRowBytes));
+#pragma unroll
+    for (int u = 0; u < kDecLoads; ++u)
+        t.v[u] = stream_words<S::kWords>(Vh + off + u * (kRowsPerWaveLoad * S::kRowBytes));
+}
+
+// Ragged last tile of a row range: rows past last_valid re-read row last_valid
+// (in bounds); the caller masks their scores.
+template <typename E, int D>
+__device__ __forceinline__ void load_tile_clamped(Tile<E, D>& t, const char* Kh, const char* Vh,
+                                                  int64_t first_row, int64_t last_valid, int rg, int c) {
+    using S = Slice<E, D>;
+    int64_t off[kDecLoads];
+#pragma unroll
+    for (int u = 0; u < kDecLoads; ++u) {
+        int64_t row = first_row + u * kRowsPerWaveLoad + rg;
+        row = row < last_valid ? row : last_valid;
+        off[u] = row * S::kRowBytes + c * S::kBytes;
+    }
+#pragma unroll
+    for (int u = 0; u < kDecLoads; ++u) t.k[u] = stream_words<S::kWords>(Kh + off[u]);
+#pragma unroll
+    for (int u = 0; u < kDecLoads; ++u) t.v[u] = stream_words<S::kWords>(Vh + off[u]);
+}
+
+// workspace layout: [counters + work queue: decode_counter_bytes] [partials]
+// partials: [B*Hq][n_splits][D + 4] floats: acc[0..D), m (log2 domain), l, two floats of padding
+// (rows start on 16-byte boundaries; no two workgroups write into the same row).
+//
+// decode_item: the share `split` (of n_splits) of one (sequence, KV head): stream
+// the rows, merge the workgroup's row groups, publish the partial and, if this
+// workgroup is the last of its KV head to finish, merge all partials into O.
+// With n_splits == 1 the workgroup's own merge already is the result.
+// Called by all threads of the workgroup; every barrier below is reached by all
+// of them or by none (the conditions are uniform).
+template <typename E, int D, int G, bool kWideMerge>
+__device__ __forceinline__ void decode_item(const char* __restrict__ Q, const char* __restrict__ Kh,
+                                            const char* __restrict__ Vh, int64_t kv_len, int64_t hq0,
+                                            int split, int n_splits, int n_splits_grid,
+                                            float scale_log2e, uint32_t* __restrict__ counter,
+                                            float* __restrict__ partial, float* __restrict__ O,
+                                            uint32_t* __restrict__ queue, uint32_t& drawn) {
+    using S = Slice<E, D>;
+    constexpr int EPL = S::kElems;
+    constexpr int W = S::kWords;
+    constexpr bool kBf16 = E::kBytes == 2;
+    constexpr float kNegInf = -INFINITY;
+    constexpr int kRow = D + 4;                      // floats per partial row (decode_partial_floats)
+    // One LDS array used twice: first the row-group tiles s_acc[16][G][D], s_m[16][G], s_l[16][G]
+    // of the workgroup's own merge, then (last workgroup of a KV head only, after two barriers)
+    // the tables of the final merge.
+    constexpr int kQuads = G * D / 4;                                   // float4 pieces of the G output rows
+    constexpr int kWays = kDecThreads / kQuads;                         // threads sharing one piece, >= 1
+    static_assert(kQuads <= kDecThreads, "more output pieces than threads");
+    constexpr int kAccFloats = kDecGroups * G * D;
+    constexpr int kTabFloats = 3 * G * kDecodeMaxSplits + kWays * G * D;
+    constexpr int kLdsFloats = kAccFloats + 2 * kDecGroups * G > kTabFloats ? kAccFloats + 2 * kDecGroups * G : kTabFloats;
+    __shared__ __attribute__((aligned(16))) float s_raw[kLdsFloats];
+    __shared__ uint32_t s_ticket;
+    float* const s_acc = s_raw;                                          // [(grp * G + g) * D + d]
+    float* const s_m = s_raw + kAccFloats;                               // [grp * G + g]
+    float* const s_l = s_m + kDecGroups * G;
+
+    const int lane = threadIdx.x % kWaveSize;
+    // the wave index is the same in all 64 lanes: keep it in a scalar register
+    // so every branch on row positions below is a scalar branch
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWaveSize);
+    const int c = lane % kRowLanes;
+    const int rg = lane / kRowLanes;
+
+    // This lane's slice of the G query rows: raw bf16 pairs for the packed dot,
+    // fp32 values otherwise.  The scale is applied to the reduced score.
+    uint32_t qw[G][W];
+    float qf[kBf16 ? 1 : G][kBf16 ? 1 : EPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        Words<W> raw = load_words<W>(Q + (hq0 + g) * S::kRowBytes + c * S::kBytes);
+#pragma unroll
+        for (int w = 0; w < W; ++w) qw[g][w] = raw.w[w];
+        if constexpr (!kBf16) widen<E, D>(raw, qf[g]);
+    }
+
+    const int64_t r1 = kv_len;                   // rows at or past r1 do not exist
+    const int lane_off = rg * S::kRowBytes + c * S::kBytes;
+
+    float m[G], l[G], acc[G][EPL];    // m: running max of the RAW score (before scaling)
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        m[g] = kNegInf;
+        l[g] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+    }
+
+    auto consume = [&](const Tile<E, D>& t, int64_t first_row, bool ragged) {
+        float s[G][kDecLoads];
+#pragma unroll
+        for (int u = 0; u < kDecLoads; ++u) {
+            if constexpr (kBf16) {
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    float a = dot2_bf16(qw[g][0], t.k[u].w[0], 0.f);
+#pragma unroll
+                    for (int w = 1; w < W; ++w) a = dot2_bf16(qw[g][w], t.k[u].w[w], a);
+                    s[g][u] = a;
+                }
+            } else {
+                float kx[EPL];
+                widen<E, D>(t.k[u], kx);
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    float a = qf[g][0] * kx[0];
+#pragma unroll
+                    for (int e = 1; e < EPL; ++e) a = fmaf(qf[g][e], kx[e], a);
+                    s[g][u] = a;
+                }
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int u = 0; u < kDecLoads; ++u) s[g][u] = row16_tree_sum(s[g][u]);
+        if (ragged) {                                    // only the last, partial tile of a range
+#pragma unroll
+            for (int u = 0; u < kDecLoads; ++u) {
+                const bool valid = first_row + u * kRowsPerWaveLoad + rg < r1;
+#pragma unroll
+                for (int g = 0; g < G; ++g) s[g][u] = valid ? s[g][u] : kNegInf;
+            }
+        }
+        float p[G][kDecLoads];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float mn = m[g];
+#pragma unroll
+            for (int u = 0; u < kDecLoads; ++u) mn = fmaxf(mn, s[g][u]);
+            // scaled max; 0 while the group has seen no valid row (avoids inf - inf)
+            const float ms = mn == kNegInf ? 0.f : mn * scale_log2e;
+            const float alpha = fast_exp2(fmaf(m[g], scale_log2e, -ms));
+            float psum = 0.f;
+#pragma unroll
+            for (int u = 0; u < kDecLoads; ++u) {
+                p[g][u] = fast_exp2(fmaf(s[g][u], scale_log2e, -ms));
+                psum += p[g][u];
+            }
+            l[g] = fmaf(l[g], alpha, psum);
+            m[g] = mn;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[g][e] *= alpha;
+        }
+#pragma unroll
+        for (int u = 0; u < kDecLoads; ++u) {
+            float vx[EPL];
+            widen<E, D>(t.v[u], vx);
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p[g][u], vx[e], acc[g][e]);
+        }
+    };
+
+    // Work assignment.  The head's rows are cut into 16-row tiles; tile t goes to
+    // workgroup (t / 4) % n_splits, wave t % 4: the workgroups of a KV head take
+    // turns on consecutive 64-row blocks.  Every workgroup therefore sweeps the
+    // whole address range of the head, which evens out the differences in
+    // memory distance between compute dies and address ranges that a
+    // contiguous range per workgroup would expose.
+    //
+    // The full tiles run through a ping-pong pipeline: tile i+1 is requested
+    // before tile i is consumed, with no branch between a load and its use, so
+    // the hardware wait counters stay exact.  The ragged last tile of the head
+    // (if any) is handled by its owner afterwards with clamped loads and
+    // masked scores.
+    {
+        const int64_t n_full = kv_len / kDecRowsPerStep;                       // full tiles in the head
+        const int64_t first_tile = (int64_t)split * kDecWaves + wave;
+        const int64_t tile_stride = (int64_t)n_splits * kDecWaves;
+        const int64_t mine = n_full > first_tile ? (n_full - first_tile + tile_stride - 1) / tile_stride : 0;
+        const int64_t kStride = tile_stride * kDecRowsPerStep;                 // rows between my tiles
+        int64_t row = first_tile * kDecRowsPerStep;
+        if (mine > 0) {
+            Tile<E, D> ta, tb;
+            // The scheduling barriers pin each batch of loads ahead of the
+            // arithmetic on the other tile; without them the compiler sinks
+            // the loads next to their first use and the prefetch is lost.
+            load_tile<E, D>(ta, Kh, Vh, row, lane_off);
+            __builtin_amdgcn_sched_barrier(0);
+            int64_t left = mine;                       // tiles not yet consumed; ta holds the first
+            while (left > 2) {
+                load_tile<E, D>(tb, Kh, Vh, row + kStride, lane_off);
+                __builtin_amdgcn_sched_barrier(0);
+                consume(ta, row, false);
+                __builtin_amdgcn_sched_barrier(0);
+                load_tile<E, D>(ta, Kh, Vh, row + 2 * kStride, lane_off);
+                __builtin_amdgcn_sched_barrier(0);
+                consume(tb, row + kStride, false);
+                __builtin_amdgcn_sched_barrier(0);
+                row += 2 * kStride;
+                left -= 2;
+            }
+            if (left == 2) {
+                load_tile<E, D>(tb, Kh, Vh, row + kStride, lane_off);
+                __builtin_amdgcn_sched_barrier(0);
+                consume(ta, row, false);
+                consume(tb, row + kStride, false);
+            } else {
+                consume(ta, row, false);
+            }
+        }
+        if (kv_len % kDecRowsPerStep != 0 && (n_full / kDecWaves) % n_splits == split &&
+            n_full % kDecWaves == wave) {
+            Tile<E, D> tt;
+            const int64_t first = n_full * kDecRowsPerStep;
+            load_tile_clamped<E, D>(tt, Kh, Vh, first, r1 - 1, rg, c);
+            consume(tt, first, true);
+        }
+    }
+
+    // Work-list launches draw the workgroup's next item here, when its rows have been streamed:
+    // early enough for the counter's latency to hide behind the merge below, late enough that
+    // items are still handed out in the order in which workgroups become free.
+    if (queue != nullptr && threadIdx.x == 0)
+        drawn = gridDim.x + __hip_atomic_fetch_add(queue, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+    // ---- merge the 16 row groups of the workgroup through LDS --------------
+    const int grp = wave * kRowsPerWaveLoad + rg;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) s_acc[(grp * G + g) * D + c * EPL + e] = acc[g][e];
+        if (c == 0) {
+            s_m[grp * G + g] = m[g] * scale_log2e;     // -inf stays -inf (scale > 0)
+            s_l[grp * G + g] = l[g];
+        }
+    }
+    __syncthreads();
+    for (int o = threadIdx.x; o < G * D; o += kDecThreads) {
+        const int g = o / D;
+        const int d = o % D;
+        float mx = kNegInf;
+#pragma unroll
+        for (int i = 0; i < kDecGroups; ++i) mx = fmaxf(mx, s_m[i * G + g]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int i = 0; i < kDecGroups; ++i) {
+            const float mi = s_m[i * G + g];
+            const float w = mi == kNegInf ? 0.f : fast_exp2(mi - mx);
+            num = fmaf(w, s_acc[(i * G + g) * D + d], num);
+            den = fmaf(w, s_l[i * G + g], den);
+        }
+        if (n_splits == 1) {
+            // the only workgroup of this KV head: its merge is the result (0 for an empty cache)
+            O[hq0 * D + o] = den > 0.f ? num / den : 0.f;
+        } else {
+            // Device-scope stores: written through to the level every compute unit
+            // of the device reads from, so the merging workgroup below sees them
+            // without any bulk cache write-back.
+            float* out = partial + ((hq0 + g) * n_splits_grid + split) * kRow;
+            publish(out + d, num);
+            if (d == 0) {
+                publish(out + D, mx);
+                publish(out + D + 1, den);
+            }
+        }
+    }
+    if (n_splits == 1) {
+        __syncthreads();          // the LDS tiles may be reused by the caller's next item
+        return;
+    }
+
+    // ---- the last workgroup of this KV head merges all row ranges ---------
+    // Hand-over protocol.  (1) Every partial is written with a device-scope
+    // atomic store (write-through: it does not stay in this die's L2).  (2)
+    // Every wave waits until its own stores have been acknowledged (vmcnt(0): a
+    // workgroup barrier alone does not wait for outstanding global stores, and
+    // the ticket below travels to a different memory channel than the partials,
+    // so without the wait it could overtake them).  (3) After the barrier one
+    // lane takes a ticket with a device-scope read-modify-write.  (4) After a
+    // second barrier the workgroup that drew the last ticket re-reads all
+    // partials with device-scope loads.  No lane ever waits on another
+    // workgroup, so nothing here can hang.
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+    __syncthreads();
+    if (threadIdx.x == 0)
+        s_ticket = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (s_ticket != (uint32_t)(n_splits - 1)) return;
+
+    constexpr int kNarrow = 8;
+    if constexpr (!kWideMerge) {
+        // Launches with at most 8 workgroups per KV head: every lane fetches, for each of its
+        // output elements (g, d), the accumulator element together with (m, l) of all
+        // workgroups at once: all loads are independent, one memory round trip, no LDS, no
+        // barrier.  (The host never pairs this variant with more than 8 workgroups.)
+        constexpr int kOut = (G * D + kDecThreads - 1) / kDecThreads;
+        float v[kOut][kNarrow], pm[kOut][kNarrow], pl[kOut][kNarrow];
+#pragma unroll
+        for (int j = 0; j < kOut; ++j) {
+            const int o = threadIdx.x + j * kDecThreads;
+            const int oo = o < G * D ? o : 0;                               // idle lanes re-read element 0
+            const int g = oo / D;
+            const int d = oo % D;
+#pragma unroll
+            for (int i = 0; i < kNarrow; ++i) {
+                const int sp = i < n_splits ? i : n_splits - 1;             // clamp: in bounds, ignored below
+                const float* p = partial + ((hq0 + g) * n_splits_grid + sp) * kRow;
+                v[j][i] = fetch(p + d);
+                pm[j][i] = fetch(p + D);
+                pl[j][i] = fetch(p + D + 1);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kOut; ++j) {
+            float bm = kNegInf;
+#pragma unroll
+            for (int i = 0; i < kNarrow; ++i)
+                if (i < n_splits) bm = fmaxf(bm, pm[j][i]);
+            float num = 0.f, den = 0.f;
+#pragma unroll
+            for (int i = 0; i < kNarrow; ++i) {
+                if (i < n_splits) {
+                    // -inf: that workgroup saw no row (cannot happen with the current
+                    // assignment, where every workgroup owns at least one row)
+                    const float w = pm[j][i] == kNegInf ? 0.f : fast_exp2(pm[j][i] - bm);
+                    num = fmaf(w, v[j][i], num);
+                    den = fmaf(w, pl[j][i], den);
+                }
+            }
+            const int o = threadIdx.x + j * kDecThreads;
+            if (o < G * D) O[hq0 * D + o] = den > 0.f ? num / den : 0.f;   // 0 for an empty cache
+        }
+    } else {
+    // Launches with more than 8 workgroups per KV head: final merge in one memory round trip.  The weights depend on (m, l) only,
+    // the sums on the accumulators only, so both are requested at once.  The
+    // (m, l) of every (query head, workgroup) go to LDS, where the per-head
+    // maximum and the weights w = 2^(m - max), w*l are formed once.  The
+    // accumulators come in as 16-byte pieces: piece q = (g, 4 consecutive d)
+    // is shared by kWays threads, thread `way` taking the workgroups way,
+    // way + kWays, ...; the kWays partial sums meet in LDS and are added in
+    // order of `way`, so the result does not depend on timing.
+    {
+        constexpr int kBatch = 16;                                       // 16-byte loads in flight per thread
+        constexpr int kEnt = (G * kDecodeMaxSplits + kDecThreads - 1) / kDecThreads;
+        float* const s_pm = s_raw;                                       // [G][n_splits] maxima
+        float* const s_w = s_pm + G * kDecodeMaxSplits;                  // [G][n_splits] weights
+        float* const s_wl = s_w + G * kDecodeMaxSplits;                  // [G][n_splits] weights * l
+        float* const s_red = s_wl + G * kDecodeMaxSplits;                // [kWays][G * D] partial sums
+        const int n_ent = G * n_splits;
+        const bool active = (int)threadIdx.x < kWays * kQuads;
+        const int way = active ? (int)threadIdx.x / kQuads : 0;
+        const int q = active ? (int)threadIdx.x % kQuads : 0;
+        const int qg = q / (D / 4);
+        // the accumulators of this KV head's G query heads are one contiguous region
+        const __amdgpu_buffer_rsrc_t region = __builtin_amdgcn_make_buffer_rsrc(
+            partial + hq0 * n_splits_grid * kRow, 0, G * n_splits_grid * kRow * (int)sizeof(float), kBufferWord3);
+        const int q_off = (qg * n_splits_grid * kRow + (q % (D / 4)) * 4) * (int)sizeof(float);
+        f32x4 v[kBatch];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            const int sp = way + i * kWays;
+            v[i] = fetch4(region, q_off + (sp < n_splits ? sp : n_splits - 1) * kRow * (int)sizeof(float));
+        }
+        float pm[kEnt], pl[kEnt];
+#pragma unroll
+        for (int t = 0; t < kEnt; ++t) {
+            const int e = threadIdx.x + t * kDecThreads;
+            const int ee = e < n_ent ? e : 0;
+            const float* p = partial + ((hq0 + ee / n_splits) * n_splits_grid + ee % n_splits) * kRow;
+            pm[t] = fetch(p + D);
+            pl[t] = fetch(p + D + 1);
+        }
+        // keep every request above ahead of the LDS work below (the compiler would otherwise
+        // sink the accumulator loads behind the two barriers, next to their first use)
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < kEnt; ++t) {
+            const int e = threadIdx.x + t * kDecThreads;
+            if (e < n_ent) s_pm[e] = pm[t];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < kEnt; ++t) {
+            const int e = threadIdx.x + t * kDecThreads;
+            if (e < n_ent) {
+                // LDS reads in independent batches of 8 (clamped index, the clamped
+                // duplicates do not change a maximum): one wait per batch, not per read
+                const float* row = s_pm + (e / n_splits) * n_splits;
+                float bm = kNegInf;
+                for (int i0 = 0; i0 < n_splits; i0 += 8) {
+                    float r[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) r[i] = row[i0 + i < n_splits ? i0 + i : n_splits - 1];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) bm = fmaxf(bm, r[i]);
+                }
+                // -inf: that workgroup saw no row (cannot happen with the current
+                // assignment, where every workgroup owns at least one row)
+                const float w = pm[t] == kNegInf ? 0.f : fast_exp2(pm[t] - bm);
+                s_w[e] = w;
+                s_wl[e] = w * pl[t];
+            }
+        }
+        __syncthreads();
+        f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+        for (int s0 = 0; s0 < n_splits; s0 += kBatch * kWays) {
+            if (s0 > 0) {
+#pragma unroll
+                for (int i = 0; i < kBatch; ++i) {
+                    const int sp = s0 + way + i * kWays;
+                    v[i] = fetch4(region, q_off + (sp < n_splits ? sp : n_splits - 1) * kRow * (int)sizeof(float));
+                }
+            }
+            float w[kBatch];                                              // independent LDS reads first
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const int sp = s0 + way + i * kWays;
+                w[i] = s_w[qg * n_splits + (sp < n_splits ? sp : n_splits - 1)];
+            }
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                if (s0 + way + i * kWays < n_splits) {
+                    sum.x = fmaf(w[i], v[i].x, sum.x);
+                    sum.y = fmaf(w[i], v[i].y, sum.y);
+                    sum.z = fmaf(w[i], v[i].z, sum.z);
+                    sum.w = fmaf(w[i], v[i].w, sum.w);
+                }
+            }
+        }
+        if (active) *reinterpret_cast<f32x4*>(s_red + way * (G * D) + q * 4) = sum;
+        __syncthreads();
+        for (int o = threadIdx.x; o < G * D; o += kDecThreads) {
+            const int g = o / D;
+            float num = 0.f, den = 0.f;
+#pragma unroll
+            for (int y = 0; y < kWays; ++y) num += s_red[y * (G * D) + o];
+            for (int i0 = 0; i0 < n_splits; i0 += 8) {
+                float r[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) r[i] = s_wl[g * n_splits + (i0 + i < n_splits ? i0 + i : n_splits - 1)];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) den += i0 + i < n_splits ? r[i] : 0.f;
+            }
+            O[hq0 * D + o] = den > 0.f ? num / den : 0.f;                 // 0 for an empty cache
+        }
+    }
+    }
+    // leave the counter ready for the next call on this workspace
+    if (threadIdx.x == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();              // the LDS tables may be reused by the caller's next item
+}
+
+// Grid launch: blockIdx.x = share of the KV head, blockIdx.y = (sequence or
+// position in the launch order) x KV head.
+template <typename E, int D, int G, bool kWideMerge>
+__global__ __launch_bounds__(kDecThreads)
+void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
+                   const char* __restrict__ Vc, int Hkv, int64_t kv_len_uniform,
+                   int64_t head_stride_bytes, const int32_t* __restrict__ lens,
+                   const int64_t* __restrict__ slot_off, const int32_t* __restrict__ seq_order,
+                   int n_splits_grid, int rows_per_wg,
+                   float scale_log2e, uint32_t* __restrict__ counters,
+                   float* __restrict__ partial, float* __restrict__ O) {
+    using S = Slice<E, D>;
+    const int split = blockIdx.x;
+    const int pair = blockIdx.y;                 // b * Hkv + hkv
+    const int hkv = pair % Hkv;
+    // Ragged batches may come with a processing order (longest sequence first):
+    // the launch index then names a position in that order, not the sequence.
+    int b = pair / Hkv;
+    if (seq_order != nullptr) {
+        const int n_seq = (int)gridDim.y / Hkv;
+        const int ob = seq_order[b];
+        b = ob < 0 ? 0 : (ob < n_seq ? ob : n_seq - 1);
+    }
+    const int Hq = Hkv * G;
+    const int64_t hq0 = (int64_t)b * Hq + (int64_t)hkv * G;   // first query head of the group
+
+    // Uniform batch: every (sequence, KV head) slab has kv_len rows and starts
+    // pair * head_stride in.  Ragged batch (lens != NULL): the cache is
+    // [Hkv][total_slots][D], head_stride is the plane stride, sequence b owns the
+    // slots slot_off[b] .. slot_off[b+1]-1 and lens[b] of them are occupied
+    // (offsets and length are clamped into the plane, so inconsistent arrays
+    // cannot lead outside the cache).  A sequence only employs as many of the
+    // launched workgroups as it has blocks of rows_per_wg rows; the others
+    // leave at once.
+    int64_t kv_len = kv_len_uniform;
+    int64_t slab = (int64_t)pair * head_stride_bytes;
+    int n_splits = n_splits_grid;
+    if (lens != nullptr) {
+        const Range slots = clamped_range(slot_off, b, head_stride_bytes / S::kRowBytes);
+        kv_len = lens[b];
+        kv_len = kv_len < 0 ? 0 : (kv_len > slots.count ? slots.count : kv_len);
+        slab = (int64_t)hkv * head_stride_bytes + slots.first * (int64_t)S::kRowBytes;
+        const int64_t need = (kv_len + rows_per_wg - 1) / rows_per_wg;
+        n_splits = need < 1 ? 1 : (need < n_splits_grid ? (int)need : n_splits_grid);
+        if (split >= n_splits) return;
+    }
+    uint32_t unused = 0;
+    decode_item<E, D, G, kWideMerge>(Q, Kc + slab, Vc + slab, kv_len, hq0, split, n_splits, n_splits_grid,
+                                     scale_log2e, counters + ((int64_t)b * Hkv + hkv), partial, O, nullptr, unused);
+}
+
+// Work-list launch for ragged batches with a known longest-first order.  A
+// fixed set of workgroups (about one per compute unit) draws items from a
+// device counter: item i is share i % n_splits_grid of KV head
+// (i / n_splits_grid) % Hkv of the sequence at position i / (n_splits_grid * Hkv)
+// of the order, so the longest sequences are handed out first and whichever
+// workgroup becomes free takes the next-longest remaining piece
+// (longest-processing-time-first list scheduling).  The next item is drawn
+// when the current one has been streamed, before its merge, which hides most
+// of the latency of the counter.  queue[0] = items drawn beyond the first round, queue[1] = workgroups that have left; the
+// last one to leave zeroes both for the next launch.  Every workgroup leaves as
+// soon as it draws an item past the end; nobody waits for anybody.
+template <typename E, int D, int G, bool kWideMerge>
+__global__ __launch_bounds__(kDecThreads)
+void decode_worklist_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
+                            const char* __restrict__ Vc, int Hkv, int n_seq, int64_t plane_stride_bytes,
+                            const int32_t* __restrict__ lens, const int64_t* __restrict__ slot_off,
+                            const int32_t* __restrict__ seq_order, int n_splits_grid, int rows_per_wg,
+                            float scale_log2e, uint32_t* __restrict__ counters, uint32_t* __restrict__ queue,
+                            float* __restrict__ partial, float* __restrict__ O) {
+    using S = Slice<E, D>;
+    __shared__ uint32_t s_item;
+    const uint32_t n_items = (uint32_t)n_seq * (uint32_t)Hkv * (uint32_t)n_splits_grid;
+    const int Hq = Hkv * G;
+    // The first gridDim.x items need no counter: workgroup i starts on item i (a simultaneous
+    // draw by every workgroup would queue up behind one memory location); the counter hands
+    // out the items from gridDim.x on.
+    uint32_t drawn = blockIdx.x;                          // thread 0 only: the item drawn ahead
+    for (;;) {
+        if (threadIdx.x == 0) s_item = drawn;
+        __syncthreads();
+        const uint32_t item = s_item;
+        __syncthreads();                                  // everyone has read s_item before it is rewritten
+        if (item >= n_items) break;
+        const int split = (int)(item % (uint32_t)n_splits_grid);
+        const int hkv = (int)((item / (uint32_t)n_splits_grid) % (uint32_t)Hkv);
+        const int pos = (int)(item / ((uint32_t)n_splits_grid * (uint32_t)Hkv));
+        const int ob = seq_order[pos];
+        const int b = ob < 0 ? 0 : (ob < n_seq ? ob : n_seq - 1);
+        const Range slots = clamped_range(slot_off, b, plane_stride_bytes / S::kRowBytes);
+        int64_t kv_len = lens[b];
+        kv_len = kv_len < 0 ? 0 : (kv_len > slots.count ? slots.count : kv_len);
+        const int64_t slab = (int64_t)hkv * plane_stride_bytes + slots.first * (int64_t)S::kRowBytes;
+        const int64_t need = (kv_len + rows_per_wg - 1) / rows_per_wg;
+        const int n_splits = need < 1 ? 1 : (need < n_splits_grid ? (int)need : n_splits_grid);
+        if (split >= n_splits) {                          // uniform: the whole workgroup skips the item
+            if (threadIdx.x == 0)
+                drawn = gridDim.x + __hip_atomic_fetch_add(&queue[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            continue;
+        }
+        const int64_t hq0 = (int64_t)b * Hq + (int64_t)hkv * G;
+        decode_item<E, D, G, kWideMerge>(Q, Kc + slab, Vc + slab, kv_len, hq0, split, n_splits, n_splits_grid,
+                                         scale_log2e, counters + ((int64_t)b * Hkv + hkv), partial, O, &queue[0], drawn);
+    }
+    if (threadIdx.x == 0) {
+        // every draw of this workgroup has returned (its value was used above), so the workgroup
+        // that finds all others gone may reset the queue
+        const uint32_t gone = __hip_atomic_fetch_add(&queue[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (gone == gridDim.x - 1) {
+            __hip_atomic_store(&queue[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&queue[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+template <typename E, int D, int G>
+l2kv_status launch_decode(const void* Q, const void* Kc, const void* Vc, int32_t B, int32_t Hq,
+                                 int32_t Hkv, int64_t kv_len, int64_t kv_head_stride,
+                                 const int32_t* lens, const int64_t* slot_off,
+                                 const int32_t* seq_order, float scale, const DecodePlan& plan,
+                                 float* O, void* workspace, hipStream_t stream) {
+    const float scale_log2e = scale * 1.4426950408889634f;
+    uint32_t* counters = static_cast<uint32_t*>(workspace);
+    (void)Hq;
+    float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + decode_counter_bytes(B, Hkv));
+    // two builds of each kernel: the final merge for at most 8 workgroups per KV head (all in
+    // registers) or for more (tables in LDS); keeping both in one kernel slows the short one down
+    const bool wide = plan.n_splits > 8;
+    if (plan.worklist_wgs > 0 && lens != nullptr && slot_off != nullptr && seq_order != nullptr) {
+        uint32_t* queue = counters + (size_t)B * (size_t)Hkv;     // two words behind the arrival counters
+        auto kernel = wide ? decode_worklist_kernel<E, D, G, true> : decode_worklist_kernel<E, D, G, false>;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)plan.worklist_wgs),
+                           dim3(kDecThreads), 0, stream, static_cast<const char*>(Q),
+                           static_cast<const char*>(Kc), static_cast<const char*>(Vc), (int)Hkv, (int)B,
+                           kv_head_stride * (int64_t)E::kBytes, lens, slot_off, seq_order,
+                           (int)plan.n_splits, (int)plan.rows_per_wg, scale_log2e, counters, queue, partial, O);
+        return launch_status();
+    }
+    dim3 grid((unsigned)plan.n_splits, (unsigned)(B * Hkv));
+    auto kernel = wide ? decode_kernel<E, D, G, true> : decode_kernel<E, D, G, false>;
+    hipLaunchKernelGGL(kernel, grid, dim3(kDecThreads), 0, stream,
+                       static_cast<const char*>(Q), static_cast<const char*>(Kc),
+                       static_cast<const char*>(Vc), (int)Hkv, kv_len,
+                       kv_head_stride * (int64_t)E::kBytes, lens, slot_off, seq_order, (int)plan.n_splits,
+                       (int)plan.rows_per_wg, scale_log2e, counters, partial, O);
+    return launch_status();
+}
+
+template <typename E, int D>
+l2kv_status decode_by_group(int G, const void* Q, const void* Kc, const void* Vc, int32_t B,
+                                   int32_t Hq, int32_t Hkv, int64_t kv_len, int64_t kv_head_stride,
+                                   const int32_t* lens, const int64_t* slot_off,
+                                   const int32_t* seq_order, float scale, const DecodePlan& plan,
+                                   float* O, void* workspace, hipStream_t stream) {
+#define L2KV_G(N)                                                                                   \
+    case N:                                                                                         \
+        return launch_decode<E, D, N>(Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride, lens, slot_off, \
+                                      seq_order, scale, plan, O, workspace, stream)
+    switch (G) {
+        L2KV_G(1); L2KV_G(2); L2KV_G(3); L2KV_G(4); L2KV_G(5); L2KV_G(6); L2KV_G(7); L2KV_G(8);
+    }
+#undef L2KV_G
+    return L2KV_ERR_SHAPE;
+}
+
+}  // namespace l2kv

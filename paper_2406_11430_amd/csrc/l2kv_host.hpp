@@ -34,17 +34,21 @@ l2kv_status compact_dispatch(const void* K, const void* V, l2kv_dtype dt, const 
 struct DecodePlan {
     int32_t n_splits;        // workgroups launched per KV head
     int32_t rows_per_wg;     // ragged batches: a sequence of n rows employs ceil(n / rows_per_wg) of them
-    int32_t lds_pad;         // bytes of unused dynamic LDS requested to keep one workgroup per compute unit
+    int32_t worklist_wgs;    // > 0: ordered ragged batch, this many workgroups draw items from a device-side list
 };
 constexpr int kDecodeMaxSplits = 256;
 constexpr int kDecodeRowTile = 64;   // rows one workgroup consumes per step (4 waves x 16)
 int32_t decode_max_splits(int64_t kv_len);
-// The decode workspace starts with one arrival counter per (sequence, KV head),
-// padded to 256 bytes; the split partials follow.
+// The decode workspace starts with one arrival counter per (sequence, KV head)
+// and the two words of the work queue of ordered ragged launches, padded to
+// 256 bytes; the split partials follow.
 inline size_t decode_counter_bytes(int32_t B, int32_t Hkv) {
-    const size_t raw = static_cast<size_t>(B) * static_cast<size_t>(Hkv) * sizeof(uint32_t);
+    const size_t raw = (static_cast<size_t>(B) * static_cast<size_t>(Hkv) + 2) * sizeof(uint32_t);
     return (raw + 255) / 256 * 256;
 }
+// One split partial = D accumulator floats, the running maximum, the denominator and two floats
+// of padding, so that every partial row starts on a 16-byte boundary and belongs to one workgroup.
+inline size_t decode_partial_floats(int32_t D) { return static_cast<size_t>(D) + 4; }
 l2kv_status workspace_init_dispatch(void* workspace, size_t bytes, hipStream_t stream);
 // Device address of the library's own scratch array on the current device (set up on first use,
 // which enqueues one fill kernel on `stream`); nullptr with *status set on failure.

@@ -125,7 +125,7 @@ def test_compact_validation(lib):
 def test_decode_validation(lib):
     f = lib.l2kv_decode_attn
     ws = lib.l2kv_decode_workspace_bytes(2, 8, 100, 128)
-    assert ws == (256 + 2 * 8 * lib.l2kv_decode_max_splits(100) * 130 * 4 + 255) // 256 * 256   # counters + partials, padded
+    assert ws == (256 + 2 * 8 * lib.l2kv_decode_max_splits(100) * 132 * 4 + 255) // 256 * 256   # counters + partials, padded
     a = (P, P, P, 1, 2, 8, 2, 100, 128, 12800, 0.0, P, P, ws, None)
 
     def call(**kw):
@@ -169,7 +169,7 @@ def test_decode_static_validation(lib):
     assert call(B=0) == E_SHAPE and call(Hq=18) == E_SHAPE and call(D=80) == E_SHAPE and call(kv_len=0) == E_SHAPE
     assert call(stride=100 * 128 - 1) == E_SHAPE and call(scale=float("inf")) == E_SHAPE
     assert call(Q=P + 4) == E_ALIGN and call(O=P + 2) == E_ALIGN
-    # beyond the scratch array: 4096 sequences x 8 heads x 130 floats of partials alone exceed 4 MiB
+    # beyond the scratch array: 4096 sequences x 8 heads x 132 floats of partials alone exceed 4 MiB
     assert call(B=4096, Hq=8, Hkv=8, kv_len=64, stride=64 * 128) == E_WS
     header = open(HEADER).read()
     assert re.search(r"#define\s+L2KV_STATIC_SCRATCH_BYTES\s+\(4u << 20\)", header)

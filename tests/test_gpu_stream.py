@@ -221,6 +221,90 @@ def test_ragged_decode_lengths_and_splits(dev):
             assert np.abs(got[s] - want).max() <= ATTN_BAR, (ns, s)
 
 
+def ragged_case(dev, rng, lens, Hkv, G, D=128, dt="bf16"):
+    slot_off = offsets([max(n, 1) + 2 for n in lens])
+    total = int(slot_off[-1])
+    K, V = rows(rng, (Hkv, total, D), dt), rows(rng, (Hkv, total, D), dt)
+    Q = rows(rng, (len(lens), Hkv * G, D), dt)
+    host = tuple(synth.as_numpy_bits(t) for t in (Q, K, V))
+    d_lens = torch.tensor(lens, dtype=torch.int32, device=dev)
+    d_off = torch.from_numpy(slot_off).to(dev)
+    return host, (Q.to(dev), K.to(dev), V.to(dev)), d_lens, d_off, slot_off
+
+
+def check_ragged(got, host, lens, slot_off, dt, tag):
+    Qn, Kn, Vn = host
+    for s, n in enumerate(lens):
+        if n == 0:
+            assert np.all(got[s] == 0), (tag, s)
+            continue
+        a = slot_off[s]
+        want = oracle.decode_attn(Qn[s:s + 1], Kn[None, :, a:a + n], Vn[None, :, a:a + n], dt)[0]
+        assert np.abs(got[s] - want).max() <= ATTN_BAR, (tag, s)
+
+
+def test_ragged_decode_work_list_with_more_items_than_workgroups(dev):
+    # ordered launches hand (sequence, KV head, share) items to one workgroup per compute unit from a
+    # device-side list: 40 sequences x 8 KV heads, whole sequences (320 items), two shares (640) and
+    # twelve shares (3840 items, the merge variant for more than 8 workgroups per head); short
+    # sequences use fewer shares than launched, so many items are skipped.  Run twice on the same
+    # workspace: the list must be left ready for the next call.
+    rng = np.random.default_rng(77)
+    lens = [int(x) for x in rng.integers(1, 3000, 40)]
+    lens[3], lens[17] = 0, 2999
+    Hkv, G = 8, 2
+    host, (Qd, Kd, Vd), d_lens, d_off, slot_off = ragged_case(dev, rng, lens, Hkv, G)
+    ws = torch.zeros(l2kv.l2kv_decode_ragged_workspace_bytes(len(lens), Hkv * G, max(lens), 128),
+                     dtype=torch.uint8, device=dev)
+    lpt = torch.empty_like(d_lens)
+    l2kv.l2kv_length_order(d_lens, lpt)
+    for rep in range(2):
+        for ns, order in ((0, lpt), (2, lpt), (12, lpt), (0, None), (12, None)):
+            O = torch.full((len(lens), Hkv * G, 128), float("nan"), dtype=torch.float32, device=dev)
+            l2kv.l2kv_decode_attn_ragged(Qd, Kd, Vd, d_lens, d_off, max(lens), O, ws, n_splits=ns, seq_order=order)
+            check_ragged(O.cpu().numpy(), host, lens, slot_off, "bf16", (rep, ns, order is not None))
+
+
+def test_ragged_decode_under_graph_capture(dev):
+    # ragged decode with and without a stored order (the latter ranks the lengths inside the call) is
+    # made of plain launches: captured after an eager warm-up, replayed on changed queries and lengths
+    # with eager calls in between, every replay bit-identical to the eager result
+    rng = np.random.default_rng(78)
+    lens = [2500, 64, 1300, 2100, 7, 900]
+    Hkv, G = 4, 4
+    host, (Qd, Kd, Vd), d_lens, d_off, slot_off = ragged_case(dev, rng, lens, Hkv, G)
+    ws = torch.zeros(l2kv.l2kv_decode_ragged_workspace_bytes(len(lens), Hkv * G, max(lens), 128),
+                     dtype=torch.uint8, device=dev)
+    order = torch.empty_like(d_lens)
+    O1 = torch.empty((len(lens), Hkv * G, 128), dtype=torch.float32, device=dev)
+    O2 = torch.empty_like(O1)
+
+    def path():
+        l2kv.l2kv_length_order(d_lens, order)
+        l2kv.l2kv_decode_attn_ragged(Qd, Kd, Vd, d_lens, d_off, max(lens), O1, ws, seq_order=order)
+        l2kv.l2kv_decode_attn_ragged(Qd, Kd, Vd, d_lens, d_off, max(lens), O2, ws)        # self-ordered
+
+    path()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        path()
+    for rep in range(3):
+        Qd.copy_(rows(rng, tuple(Qd.shape), "bf16").to(dev))
+        new_lens = [max(1, n - 11 * rep) for n in lens]
+        d_lens.copy_(torch.tensor(new_lens, dtype=torch.int32))
+        path()
+        torch.cuda.synchronize()
+        want1, want2 = O1.clone(), O2.clone()
+        O1.fill_(float("nan")); O2.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O1.view(torch.int32), want1.view(torch.int32)), rep
+        assert torch.equal(O2.view(torch.int32), want2.view(torch.int32)), rep
+        host_now = (synth.as_numpy_bits(Qd), host[1], host[2])
+        check_ragged(O1.cpu().numpy(), host_now, new_lens, slot_off, "bf16", ("graph", rep))
+
+
 def test_inconsistent_device_arrays_stay_inside_the_described_tensors(dev):
     # Offsets and lengths live on the device and cannot be validated by the host; the kernels force
     # them into the tensors the call describes.  Every tensor here is allocated with one spare plane

@@ -5,14 +5,20 @@ One "step" is one pass of the whole hot path over one synthetic batch of the
 32k-context Llama-3-8B-shaped GQA workload (config C3): compress every layer's
 cache once (key norms -> lowest-norm selection -> K/V compaction), then run 64
 decode steps of single-query GQA attention over the compacted cache of all 32
-layers.  Inputs are resident in HBM before the timed region starts.
+layers.  The cache is static during decoding: no row is appended per decode
+step (the streaming workload C5 is the one that appends and evicts).  Inputs
+are resident in HBM before the timed region starts.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3]
 
 Prints ONE JSON line: whole-path effective HBM GB/s (algorithmic bytes / wall
 time), microseconds per decode step, the roofline of the dominant kernel
-(decode attention) from HIP events on the launch stream, and the CPU oracle
-timed on a bounded sample of the same workload.
+(decode attention) from HIP events on the launch stream, the CPU oracle timed
+on a bounded sample of the same workload (one thread, and threads over heads on
+the host cores this process may use), and -- in the default run -- one short
+pass each of the 131k-token retrieval workload (C4) and the ragged streaming
+workload (C5) under "other_workloads", each with a GPU-vs-oracle check of a
+sample.
 """
 from __future__ import annotations
 
@@ -21,6 +27,7 @@ import json
 import os
 import sys
 import time
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 import torch
@@ -32,13 +39,40 @@ if ROOT not in sys.path:
 import paper_2406_11430_amd as l2kv            # noqa: E402
 from paper_2406_11430_amd import synth         # noqa: E402
 
-HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
+HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak (8 TB/s): the figure every fraction here is taken of
 
 # HBM bytes of ONE decode-attention launch at the C3 per-layer shape, from two
 # rocprofv3 --pmc runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a
 # plain 1 GiB copy in the same runs): profiles/hot_path_hbm_traffic_pmc.md.
-# Offline measurement; reported only when the timed shape is that shape.
-MEASURED_DECODE_TRAFFIC_BYTES = {("bf16", 4, 8, 32, 128, 16384): (263036 + 539) * 1024}
+# A constant from that offline profile, not something this run measures;
+# reported only when the timed shape is that shape.
+PROFILED_DECODE_TRAFFIC_BYTES = {("bf16", 4, 8, 32, 128, 16384): (263036 + 539) * 1024}
+
+
+def host_threads():
+    """Threads the CPU baseline may use: the cores this process is allowed on,
+    at most 16 (the host share that goes with one GPU)."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    return max(1, min(16, n))
+
+
+def device_facts(dev):
+    """What the device reports about itself, printed next to the peak used."""
+    p = torch.cuda.get_device_properties(dev)
+    info = l2kv.l2kv_device_info()
+    clock_khz, bus_bits = info["memory_clock_khz"], info["memory_bus_bits"]
+    from_props = None
+    if clock_khz and bus_bits:
+        # HBM3E moves 4 bits per pin per reported memory clock (8 Gb/s per pin at 2000 MHz)
+        from_props = round(4.0 * clock_khz * 1e3 * bus_bits / 8 / 1e9, 1)
+    return {"name": p.name, "compute_units": info["compute_units"],
+            "memory_GiB": round(p.total_memory / 2 ** 30, 1),
+            "memory_clock_MHz": None if not clock_khz else round(clock_khz / 1e3, 1),
+            "memory_bus_bits": bus_bits, "GBps_from_bus_bits_x_clock_x_4_per_clock": from_props,
+            "peak_used_GBps": HBM_PEAK_GBPS}
 
 
 # ----------------------------------------------------------------- byte model
@@ -122,44 +156,66 @@ class Workload:
 
 
 # --------------------------------------------------------------- CPU baseline
-def cpu_baseline(w: Workload, layers, dec_steps):
+def cpu_baseline(w: Workload, layers, dec_steps, threads):
     """Time the CPU oracle, as it stands, on a bounded sample: the full
     compression of `layers` layers plus `dec_steps` decode steps on each of
-    them.  Also compares the GPU results of the same sample with the oracle."""
+    them.  Two legs over the same sample: one thread (a whole layer per oracle
+    call), and `threads` threads over the (sequence, KV head) pairs of a layer
+    (the same oracle calls on one head each; ctypes releases the interpreter
+    lock around them).  The one-thread leg also compares the GPU results of the
+    sample with the oracle's."""
     import oracle
     cfg = w.cfg
-    t_total = 0.0
+    G = cfg.Hq // cfg.Hkv
+    t_one = t_all = 0.0
     bytes_total = 0
     worst = 0.0
-    idx_equal = True
-    rows_equal = True
+    idx_equal = rows_equal = True
+    heads = [(b, h) for b in range(cfg.B) for h in range(cfg.Hkv)]
     for layer in layers:
         Kn = synth.as_numpy_bits(w.K[layer])
         Vn = synth.as_numpy_bits(w.V[layer])
+        Qn = [synth.as_numpy_bits(w.Q[step, layer]) for step in range(dec_steps)]
+        bytes_total += sum(compress_bytes_per_layer(cfg, w.k)) + dec_steps * decode_bytes_per_layer(cfg, w.k)
+        # ---- one thread
         t0 = time.perf_counter()
         n32, _, idx, Kc, Vc = oracle.compress(Kn, Vn, cfg.dtype, cfg.keep_ratio)
-        t_total += time.perf_counter() - t0
-        bytes_total += sum(compress_bytes_per_layer(cfg, w.k))
+        t_one += time.perf_counter() - t0
         idx_equal &= bool(np.array_equal(idx, w.idx[layer].cpu().numpy()))
         rows_equal &= bool(np.array_equal(Kc, synth.as_numpy_bits(w.Kc[layer])))
         rows_equal &= bool(np.array_equal(Vc, synth.as_numpy_bits(w.Vc[layer])))
         for step in range(dec_steps):
-            Qn = synth.as_numpy_bits(w.Q[step, layer])
             t0 = time.perf_counter()
-            want = oracle.decode_attn(Qn, Kc, Vc, cfg.dtype)
-            t_total += time.perf_counter() - t0
-            bytes_total += decode_bytes_per_layer(cfg, w.k)
+            want = oracle.decode_attn(Qn[step], Kc, Vc, cfg.dtype)
+            t_one += time.perf_counter() - t0
             O = torch.empty((cfg.B, cfg.Hq, cfg.D), dtype=torch.float32, device=w.dev)
             l2kv.l2kv_decode_attn(w.Q[step, layer], w.Kc[layer], w.Vc[layer], O, w.dec_ws)
             worst = max(worst, float(np.abs(O.cpu().numpy() - want).max()))
-    return {
-        "value": bytes_total / t_total / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-        "sample": "%s: full compress of layer(s) %s + %d decode step(s) on each; %.1f s of CPU time"
-                  % (cfg.name, list(layers), dec_steps, t_total),
-        "seconds": t_total,
+        del n32, idx, Kc, Vc
+        # ---- threads over heads
+        if threads > 1:
+            def one_head(bh):
+                b, h = bh
+                _, _, _, kc, vc = oracle.compress(Kn[b:b + 1, h:h + 1], Vn[b:b + 1, h:h + 1], cfg.dtype, cfg.keep_ratio)
+                for step in range(dec_steps):
+                    oracle.decode_attn(np.ascontiguousarray(Qn[step][b:b + 1, h * G:(h + 1) * G]), kc, vc, cfg.dtype)
+            t0 = time.perf_counter()
+            with ThreadPoolExecutor(max_workers=threads) as pool:
+                list(pool.map(one_head, heads))
+            t_all += time.perf_counter() - t0
+    sample = "%s: full compress of layer(s) %s + %d decode step(s) on each" % (cfg.name, list(layers), dec_steps)
+    one = {
+        "value": bytes_total / t_one / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": "%s; %.1f s of CPU time" % (sample, t_one), "seconds": t_one,
         "gpu_vs_oracle_on_sample": {"kept_idx_equal": idx_equal, "compacted_rows_equal": rows_equal,
                                     "attn_max_abs_err": worst},
     }
+    many = None
+    if threads > 1:
+        many = {"value": bytes_total / t_all / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+                "sample": "%s; threads over the %d (sequence, KV head) pairs of a layer; %.1f s wall" % (sample, len(heads), t_all),
+                "seconds": t_all, "host_cpu_count": os.cpu_count()}
+    return one, many
 
 
 # ------------------------------------------------------- streaming workload (C5)
@@ -272,24 +328,85 @@ class StreamWorkload:
         return attn, other
 
 
-def main_stream(args, dev):
-    cfg = synth.STREAM_CONFIGS[args.workload]
-    overridden = False
-    if args.layers:
-        cfg, overridden = cfg.scaled(L=args.layers), True
-    if args.decode_steps:
-        cfg, overridden = cfg.scaled(decode_steps=args.decode_steps), True
+def stream_parity_sample(w: "StreamWorkload", n_heads=5, steps=4):
+    """GPU vs oracle on sampled (plane, sequence) heads of the streaming batch: the
+    oracle compresses the sampled prompts and replays the first decode steps
+    token by token (append, attend, evict to budget).  Kept token ids, slot
+    contents and lengths must agree exactly; the attention error is returned."""
+    import oracle
+    cfg = w.cfg
+    w.compress()
+    torch.cuda.synchronize()
+    lens = w.lens0
+    rng = np.random.default_rng(55)
+    P = cfg.L * cfg.Hkv
+    samples = {(0, int(np.argmax(lens))), (P - 1, int(np.argmin(lens)))}
+    while len(samples) < n_heads:
+        samples.add((int(rng.integers(P)), int(rng.integers(cfg.n_seq))))
+    in_off, out_off, slot_off = (t.cpu().numpy() for t in (w.in_off, w.out_off, w.slot_off))
+    caps = np.diff(slot_off)
+    heads, idx_equal = {}, True
+    t_cpu = 0.0
+    for (p, s) in sorted(samples):
+        a, b = in_off[s], in_off[s + 1]
+        Kn, Vn = synth.as_numpy_bits(w.K[p, a:b]), synth.as_numpy_bits(w.V[p, a:b])
+        t0 = time.perf_counter()
+        n32, _ = oracle.norms(Kn[None], cfg.dtype)
+        kept = oracle.select(n32, w.k0[s])[0]
+        h = oracle.StreamHead(int(caps[s]), cfg.D, cfg.dtype)
+        h.load(Kn[kept], Vn[kept], n32[0, kept], kept.astype(np.int32))
+        t_cpu += time.perf_counter() - t0
+        idx_equal &= bool(np.array_equal(w.idx[p, out_off[s]:out_off[s + 1]].cpu().numpy(), kept))
+        heads[(p, s)] = h
+
+    def slots_equal():
+        ok = True
+        lens_dev = w.lensA.cpu().numpy()
+        for (p, s), h in heads.items():
+            n, a = len(h), slot_off[s]
+            ids, Kk, Vk, nk = h.kept()
+            pc = w.pc[p, a:a + n].cpu().numpy()
+            order = np.argsort(pc, kind="stable")
+            ok &= int(lens_dev[s]) == n and bool(np.array_equal(pc[order], ids))
+            ok &= bool(np.array_equal(synth.as_numpy_bits(w.Kc[p, a:a + n])[order], Kk))
+            ok &= bool(np.array_equal(synth.as_numpy_bits(w.Vc[p, a:a + n])[order], Vk))
+            ok &= bool(np.array_equal(w.nc[p, a:a + n].cpu().numpy()[order].view(np.uint32), nk.view(np.uint32)))
+        return ok
+
+    G, worst = cfg.Hq // cfg.Hkv, 0.0
+    cache_equal = slots_equal()
+    for t in range(min(steps, cfg.decode_steps)):
+        w.decode_step(t)
+        torch.cuda.synchronize()
+        O = w.O.cpu().numpy()
+        for (p, s), h in heads.items():
+            layer, hk = p // cfg.Hkv, p % cfg.Hkv
+            kn = synth.as_numpy_bits(w.Knew[t, layer, s, hk])
+            vn = synth.as_numpy_bits(w.Vnew[t, layer, s, hk])
+            qn = synth.as_numpy_bits(w.Q[t, layer, s, hk * G:(hk + 1) * G])
+            t0 = time.perf_counter()
+            h.append(kn, vn, lens[s] + t)
+            want = h.attend(qn)
+            h.evict_to(w.budgets_host[t][s])
+            t_cpu += time.perf_counter() - t0
+            worst = max(worst, float(np.abs(O[layer, s, hk * G:(hk + 1) * G] - want).max()))
+        cache_equal &= slots_equal()
+    return {"heads": sorted(samples), "decode_steps": min(steps, cfg.decode_steps), "kept_idx_equal": idx_equal,
+            "slot_cache_equal": cache_equal, "attn_max_abs_err": worst, "oracle_seconds": round(t_cpu, 2)}
+
+
+def run_stream(cfg, dev, steps, warmup, overridden=False, use_order=True, parity=True):
     w = StreamWorkload(cfg, dev)
-    w.use_order = not args.no_seq_order
+    w.use_order = use_order
     attn_bytes, other_bytes = w.decode_bytes()
     comp_bytes = w.compress_bytes()
     step_bytes = comp_bytes + attn_bytes + other_bytes
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         w.step()
     torch.cuda.synchronize()
     marks = []
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
         e[0].record()
         w.compress()
@@ -300,20 +417,21 @@ def main_stream(args, dev):
         marks.append(e)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    comp_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in marks]))
-    dec_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in marks]))
-    value = step_bytes / (wall / args.steps) / 1e9
+    comp_ms = float(np.median([e[0].elapsed_time(e[1]) for e in marks]))
+    dec_ms = float(np.median([e[1].elapsed_time(e[2]) for e in marks]))
+    value = step_bytes / (wall / steps) / 1e9
     achieved = (attn_bytes + other_bytes) / dec_ms / 1e6
     out = {
         "metric": "compress+decode effective HBM GB/s", "value": round(value, 1), "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(wall * 1e3 / args.steps, 3), "higher_is_better": True, "scaling": "weak",
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": round(wall * 1e3 / steps, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name + (" (size overridden)" if overridden else ""), "layers": cfg.L,
                    "sequences": cfg.n_seq, "prompt_lengths": "uniform[%d, %d], seeded (sum %d)" % (cfg.len_lo, cfg.len_hi, w.total),
                    "kv_heads": cfg.Hkv, "q_heads": cfg.Hq, "head_dim": cfg.D, "keep_ratio": cfg.keep_ratio,
                    "decode_steps": cfg.decode_steps,
-                   "step": "ragged compress of all prompts + decode_steps x (append, layers x ragged attention, evict)"},
+                   "step": "ragged compress of all prompts + decode_steps x (append one row per sequence, "
+                           "layers x ragged attention, evict to keep_count(tokens seen))"},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "us_per_decode_step": round(dec_ms * 1e3 / cfg.decode_steps, 2),
         "phases": {"compress": {"ms": round(comp_ms, 4), "GBps": round(comp_bytes / comp_ms / 1e6, 1)},
@@ -323,6 +441,23 @@ def main_stream(args, dev):
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
                      "bytes_per_decode_step": (attn_bytes + other_bytes) // cfg.decode_steps},
     }
+    if parity:
+        out["gpu_vs_oracle_on_sample"] = stream_parity_sample(w)
+    del w
+    torch.cuda.empty_cache()
+    return out
+
+
+def main_stream(args, dev):
+    cfg = synth.STREAM_CONFIGS[args.workload]
+    overridden = False
+    if args.layers:
+        cfg, overridden = cfg.scaled(L=args.layers), True
+    if args.decode_steps:
+        cfg, overridden = cfg.scaled(decode_steps=args.decode_steps), True
+    out = run_stream(cfg, dev, args.steps, args.warmup, overridden, not args.no_seq_order,
+                     parity=not args.no_cpu_baseline)
+    out["device"] = device_facts(dev)
     print(json.dumps(out))
 
 
@@ -404,6 +539,8 @@ def main():
     ap.add_argument("--no-seq-order", action="store_true",
                     help="streaming workloads: pass no stored launch order to the ragged attention calls "
                          "(the library then works one out per call; for comparisons)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="default C3 run only: skip the short C4 and C5 passes reported under other_workloads")
     ap.add_argument("--alr", action="store_true",
                     help="time the attention-loss analysis (norm ranks + losses + Y) at the workload's "
                          "per-layer shape instead of the hot path")
@@ -432,8 +569,21 @@ def main():
         cfg, overridden = cfg.scaled(L=args.layers), True
     if args.decode_steps:
         cfg, overridden = cfg.scaled(decode_steps=args.decode_steps), True
+    out = run_uniform(cfg, dev, args.steps, args.warmup, overridden, args.decode_splits, args.copy_probe,
+                      0 if args.no_cpu_baseline else args.cpu_layers, args.cpu_decode_steps)
+    out["device"] = device_facts(dev)
+    if args.workload == "C3" and not overridden and not args.no_other_workloads:
+        # one short pass each of the other two full-size workloads, same fields, so that their
+        # figures come from the same run on the same box as the headline
+        out["other_workloads"] = [
+            run_uniform(synth.CONFIGS["C4"], dev, 2, 1, False, 0, False, 0 if args.no_cpu_baseline else 1, 1),
+            run_stream(synth.STREAM_CONFIGS["C5"], dev, 1, 1, parity=not args.no_cpu_baseline),
+        ]
+    print(json.dumps(out))
 
-    w = Workload(cfg, dev, args.decode_splits)
+
+def run_uniform(cfg, dev, steps, warmup, overridden, decode_splits, copy_probe, cpu_layers, cpu_decode_steps):
+    w = Workload(cfg, dev, decode_splits)
     k = w.k
     nb, sb, cb = compress_bytes_per_layer(cfg, k)
     comp_bytes = (nb + sb + cb) * cfg.L
@@ -441,14 +591,14 @@ def main():
     dec_bytes = dec_bytes_layer * cfg.L * cfg.decode_steps
     step_bytes = comp_bytes + dec_bytes
 
-    if args.copy_probe:
+    if copy_probe:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         w.step()
     torch.cuda.synchronize()
 
@@ -456,7 +606,7 @@ def main():
     marks = []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         e = [ev() for _ in range(5)]
         e[0].record()
         l2kv.l2kv_norms(w.K, w.norms)
@@ -472,17 +622,20 @@ def main():
     wall = time.perf_counter() - t0
 
     ms = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in marks])  # [steps][4]
-    norms_ms, select_ms, compact_ms, decode_ms = ms.mean(axis=0)
-    ms_per_step = wall * 1e3 / args.steps
-    value = step_bytes / (wall / args.steps) / 1e9
+    norms_ms, select_ms, compact_ms, decode_ms = (float(x) for x in np.median(ms, axis=0))
+    ms_per_step = wall * 1e3 / steps
+    value = step_bytes / (wall / steps) / 1e9
     n_decode_launch = cfg.L * cfg.decode_steps
     us_per_layer_call = decode_ms * 1e3 / n_decode_launch
     achieved = dec_bytes_layer / (us_per_layer_call * 1e-6) / 1e9
+    # the norm pass is this library's own pure read stream (it reads K once and writes 1.6 % of
+    # that): what a read-only kernel reaches on this machine in this run
+    read_stream = nb * cfg.L / norms_ms / 1e6
 
     out = {
         "metric": "compress+decode effective HBM GB/s",
         "value": round(value, 1), "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
@@ -491,34 +644,45 @@ def main():
             "layers": cfg.L, "batch": cfg.B, "kv_heads": cfg.Hkv, "q_heads": cfg.Hq,
             "head_dim": cfg.D, "cached_tokens": cfg.T, "keep_ratio": cfg.keep_ratio, "kept": k,
             "decode_steps": cfg.decode_steps,
-            "step": "compress all layers once + decode_steps x layers decode-attention calls",
-            "decode_splits": args.decode_splits or "library default",
+            "step": "compress all layers once + decode_steps x layers decode-attention calls over the "
+                    "static compacted cache (no row appended per decode step)",
+            "decode_splits": decode_splits or "library default",
         },
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "us_per_decode_step": round(decode_ms * 1e3 / cfg.decode_steps, 2),
         "us_per_decode_layer": round(us_per_layer_call, 3),
+        "phase_times": "median over the timed steps (HIP events)",
         "phases": {
-            "norms": {"ms": round(float(norms_ms), 4), "GBps": round(nb * cfg.L / norms_ms / 1e6, 1)},
-            "select": {"ms": round(float(select_ms), 4), "GBps": round(sb * cfg.L / select_ms / 1e6, 1)},
-            "compact": {"ms": round(float(compact_ms), 4), "GBps": round(cb * cfg.L / compact_ms / 1e6, 1)},
-            "compress": {"ms": round(float(norms_ms + select_ms + compact_ms), 4),
+            "norms": {"ms": round(norms_ms, 4), "GBps": round(nb * cfg.L / norms_ms / 1e6, 1)},
+            "select": {"ms": round(select_ms, 4), "GBps": round(sb * cfg.L / select_ms / 1e6, 1)},
+            "compact": {"ms": round(compact_ms, 4), "GBps": round(cb * cfg.L / compact_ms / 1e6, 1)},
+            "compress": {"ms": round(norms_ms + select_ms + compact_ms, 4),
                          "GBps": round(comp_bytes / (norms_ms + select_ms + compact_ms) / 1e6, 1)},
-            "decode": {"ms": round(float(decode_ms), 4), "GBps": round(dec_bytes / decode_ms / 1e6, 1)},
+            "decode": {"ms": round(decode_ms, 4), "GBps": round(dec_bytes / decode_ms / 1e6, 1)},
         },
         "roofline": {
             "kernel": "decode attention (one l2kv_decode_attn call on one layer)",
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": MEASURED_DECODE_TRAFFIC_BYTES.get((cfg.dtype, cfg.B, cfg.Hkv, cfg.Hq, cfg.D, k)),
-            "traffic_unit": "bytes per launch (rocprofv3 --pmc, see profiles/)",
+            "read_stream_GBps": round(read_stream, 1),
+            "pct_of_read_stream": round(100.0 * achieved / read_stream, 1),
+            "read_stream": "the norm pass of the same run (reads K once): the read-only rate reached here",
+            "traffic": PROFILED_DECODE_TRAFFIC_BYTES.get((cfg.dtype, cfg.B, cfg.Hkv, cfg.Hq, cfg.D, k)),
+            "traffic_unit": "bytes per launch; constant from an offline rocprofv3 --pmc profile "
+                            "(profiles/hot_path_hbm_traffic_pmc.md), not measured by this run",
             "bytes_per_launch": dec_bytes_layer, "us_per_launch": round(us_per_layer_call, 3),
             "timing": "HIP events on the launch stream around all %d calls of each step" % n_decode_launch,
         },
     }
-    if not args.no_cpu_baseline:
-        layers = list(range(min(args.cpu_layers, cfg.L)))
-        out["cpu_baseline"] = cpu_baseline(w, layers, min(args.cpu_decode_steps, cfg.decode_steps))
-    print(json.dumps(out))
+    if cpu_layers > 0:
+        layers = list(range(min(cpu_layers, cfg.L)))
+        one, many = cpu_baseline(w, layers, min(cpu_decode_steps, cfg.decode_steps), host_threads())
+        out["cpu_baseline"] = one
+        if many is not None:
+            out["cpu_baseline_all_cores"] = many
+    del w
+    torch.cuda.empty_cache()
+    return out
 
 
 if __name__ == "__main__":

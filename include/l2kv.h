@@ -162,6 +162,8 @@ l2kv_status l2kv_compact(const void* K, const void* V, l2kv_dtype dt,
  *              them zero again, so the buffer can be reused call after call
  *              for any shape it is large enough for.  Two calls that share a
  *              workspace must not overlap in time.
+ * The rows need not have been compacted: an uncompressed layer is attended to
+ * in place by passing the original cache and kv_len = T.
  * Arithmetic: fp32 accumulation throughout; for bf16 caches q.k is formed with
  * the packed bf16 dot instruction (exact bf16 products, fp32 sum), for fp32
  * caches with fp32 FMAs; softmax and the value sum are fp32.
@@ -328,6 +330,13 @@ l2kv_status l2kv_stream_evict(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, in
  *             made of plain kernel launches and may be captured into a graph.
  *   max_len : an upper bound of all lens[s] (sizes the decomposition and the
  *             workspace; rows beyond it are still attended to)
+ * A layer that is left uncompressed (Sec. 4 skips the first layers by default)
+ * needs no copy at all: pass its prompt tensors as Kc, Vc with slot_offsets =
+ * the prompt offsets, total_slots = total_tokens and lens[s] = T_s.  Per-head
+ * keep counts (the outlook of Sec. 8) are the same call with every (sequence,
+ * KV head) laid out as one "sequence" of a single plane (Hkv = 1, Hq = the
+ * query group), as produced by l2kv_select_ragged / l2kv_compact_ragged with one
+ * k per head.
  *   n_splits: 0 = library default
  *   workspace: l2kv_decode_ragged_workspace_bytes(n_seq, Hq, max_len, D) bytes
  *              (the uniform workspace plus room for that order), same
@@ -408,6 +417,16 @@ l2kv_status l2kv_alr(const void* Q, const void* K, l2kv_dtype dt, const int32_t*
                      size_t workspace_bytes, void* stream);
 
 size_t l2kv_alr_workspace_bytes(int32_t B, int32_t Hq, int64_t T);
+
+/*
+ * What the current HIP device reports about itself (host function, no kernel):
+ * compute units, peak memory clock in kHz and memory bus width in bits, so
+ * that a benchmark can print them next to the bandwidth peak it assumes.  Any
+ * of the three pointers may be NULL.  Errors: LAUNCH if the runtime refuses
+ * the query.
+ */
+l2kv_status l2kv_device_info(int32_t* h_compute_units, int32_t* h_memory_clock_khz,
+                             int32_t* h_memory_bus_bits);
 
 /* Static, NUL-terminated description of a status code. */
 const char* l2kv_status_string(l2kv_status s);

@@ -71,6 +71,7 @@ SIGNATURES = {
                            C.c_int64, C.c_int32, C.c_int64, C.c_float, C.c_int64, C.c_void_p, C.c_void_p,
                            C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "l2kv_alr_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int64]),
+    "l2kv_device_info": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "l2kv_status_string": (C.c_char_p, [C.c_int]),
     "l2kv_version": (C.c_int32, []),
 }
@@ -155,6 +156,13 @@ def l2kv_decode_workspace_init(workspace: torch.Tensor, stream=None) -> None:
     _dev(workspace)
     _check("l2kv_decode_workspace_init", lib().l2kv_decode_workspace_init(
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def l2kv_device_info() -> dict:
+    """Compute units, peak memory clock (kHz) and memory bus width (bits) of the current device."""
+    cu, clk, bus = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    _check("l2kv_device_info", lib().l2kv_device_info(C.byref(cu), C.byref(clk), C.byref(bus)))
+    return {"compute_units": cu.value, "memory_clock_khz": clk.value, "memory_bus_bits": bus.value}
 
 
 def l2kv_version() -> int:

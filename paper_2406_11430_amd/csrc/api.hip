@@ -397,6 +397,29 @@ l2kv_status l2kv_alr(const void* Q, const void* K, l2kv_dtype dt, const int32_t*
                         workspace, static_cast<hipStream_t>(stream));
 }
 
+l2kv_status l2kv_device_info(int32_t* h_compute_units, int32_t* h_memory_clock_khz, int32_t* h_memory_bus_bits) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return L2KV_ERR_LAUNCH;
+    }
+    const struct { int32_t* out; hipDeviceAttribute_t attr; } want[] = {
+        {h_compute_units, hipDeviceAttributeMultiprocessorCount},
+        {h_memory_clock_khz, hipDeviceAttributeMemoryClockRate},
+        {h_memory_bus_bits, hipDeviceAttributeMemoryBusWidth},
+    };
+    for (const auto& w : want) {
+        if (w.out == nullptr) continue;
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, w.attr, dev) != hipSuccess) {
+            (void)hipGetLastError();
+            return L2KV_ERR_LAUNCH;
+        }
+        *w.out = v;
+    }
+    return L2KV_OK;
+}
+
 const char* l2kv_status_string(l2kv_status s) {
     switch (s) {
         case L2KV_OK: return "ok";

@@ -543,6 +543,78 @@ def test_per_head_keep_counts_through_the_ragged_entry_points(dev):
     assert np.array_equal(idx[0, :T].cpu().numpy(), np.arange(T))   # the skipped head is untouched
 
 
+def test_per_head_keep_counts_end_to_end_through_decode(dev):
+    # per-head keep counts all the way: every (sequence, KV head) is one "sequence" of a single-plane
+    # ragged batch with its own k (one head keeps everything, one keeps a single row), compacted
+    # into a slot cache and attended to with Hkv = 1, Hq = G -- the output rows then come out in
+    # the [B][Hq][D] order of the uniform call.  Each head against the oracle on ITS kept rows.
+    rng = np.random.default_rng(32)
+    B, Hkv, G, T, D = 2, 3, 4, 900, 128
+    n_heads = B * Hkv
+    ks = [900, 450, 1, 123, 899, 64]
+    K = rand_cache(rng, (B, Hkv, T, D), "bf16")
+    V = rand_cache(rng, (B, Hkv, T, D), "bf16")
+    Q = rand_cache(rng, (B, Hkv * G, D), "bf16")
+    Kd = to_dev(K, "bf16", dev).view(1, n_heads * T, D)
+    Vd = to_dev(V, "bf16", dev).view(1, n_heads * T, D)
+    Qd = to_dev(Q, "bf16", dev).view(n_heads, G, D)
+    in_off = torch.arange(n_heads + 1, dtype=torch.int64, device=dev) * T
+    out_off = torch.tensor([0] + list(np.cumsum(ks)), dtype=torch.int64, device=dev)
+    norms = gpu_norms(Kd)
+    idx = torch.empty((1, sum(ks)), dtype=torch.int32, device=dev)
+    l2kv.l2kv_select_ragged(norms, in_off, out_off, T, idx)
+    Kc = torch.zeros((1, sum(ks), D), dtype=torch.bfloat16, device=dev)
+    Vc = torch.zeros_like(Kc)
+    nc = torch.zeros((1, sum(ks)), dtype=torch.float32, device=dev)
+    pc = torch.zeros((1, sum(ks)), dtype=torch.int32, device=dev)
+    l2kv.l2kv_compact_ragged(Kd, Vd, norms, idx, in_off, out_off, max(ks), out_off, Kc, Vc, nc, pc)
+    lens = torch.tensor(ks, dtype=torch.int32, device=dev)
+    ws = torch.zeros(l2kv.l2kv_decode_ragged_workspace_bytes(n_heads, G, max(ks), D), dtype=torch.uint8, device=dev)
+    for ns in (0, 1, 3):
+        O = torch.full((n_heads, G, D), float("nan"), dtype=torch.float32, device=dev)
+        l2kv.l2kv_decode_attn_ragged(Qd, Kc, Vc, lens, out_off, max(ks), O, ws, n_splits=ns)
+        got = O.cpu().numpy().reshape(B, Hkv * G, D)
+        n32, _ = oracle.norms(K, "bf16")
+        for b in range(B):
+            for h in range(Hkv):
+                k = ks[b * Hkv + h]
+                kept = oracle.select(n32[b, h][None], k)[0]
+                want = oracle.decode_attn(Q[b:b + 1, h * G:(h + 1) * G], K[b:b + 1, h:h + 1][:, :, kept],
+                                          V[b:b + 1, h:h + 1][:, :, kept], "bf16")[0]
+                err = float(np.abs(got[b, h * G:(h + 1) * G] - want).max())
+                assert err <= ATTN_BAR, (ns, b, h, err)
+
+
+def test_uncompressed_layers_are_decoded_in_place(dev):
+    # Sec. 4 leaves the first layers uncompressed by default.  Such a layer costs nothing in the
+    # compression step: decode attention runs straight on the original cache -- the uniform call
+    # with kv_len = T, the ragged call with the prompt tensors as the slot cache (slot offsets =
+    # prompt offsets, every slot occupied) -- and equals full attention.
+    rng = np.random.default_rng(33)
+    B, Hkv, G, T, D = 2, 2, 4, 1100, 128
+    K, V = rand_cache(rng, (B, Hkv, T, D), "bf16"), rand_cache(rng, (B, Hkv, T, D), "bf16")
+    Q = rand_cache(rng, (B, Hkv * G, D), "bf16")
+    want = oracle.decode_attn(Q, K, V, "bf16")
+    got = gpu_decode(to_dev(Q, "bf16", dev), to_dev(K, "bf16", dev), to_dev(V, "bf16", dev)).cpu().numpy()
+    assert np.abs(got - want).max() <= ATTN_BAR
+    # ragged: three prompts of different lengths back to back in every head plane
+    Ts = [700, 64, 1333]
+    off = np.concatenate([[0], np.cumsum(Ts)]).astype(np.int64)
+    Kr, Vr = rand_cache(rng, (Hkv, int(off[-1]), D), "bf16"), rand_cache(rng, (Hkv, int(off[-1]), D), "bf16")
+    Qr = rand_cache(rng, (len(Ts), Hkv * G, D), "bf16")
+    lens = torch.tensor(Ts, dtype=torch.int32, device=dev)
+    d_off = torch.from_numpy(off).to(dev)
+    ws = torch.zeros(l2kv.l2kv_decode_ragged_workspace_bytes(len(Ts), Hkv * G, max(Ts), D), dtype=torch.uint8, device=dev)
+    O = torch.full((len(Ts), Hkv * G, D), float("nan"), dtype=torch.float32, device=dev)
+    l2kv.l2kv_decode_attn_ragged(to_dev(Qr, "bf16", dev), to_dev(Kr, "bf16", dev), to_dev(Vr, "bf16", dev), lens, d_off,
+                                 max(Ts), O, ws)
+    got = O.cpu().numpy()
+    for s, n in enumerate(Ts):
+        a = off[s]
+        w = oracle.decode_attn(Qr[s:s + 1], Kr[None, :, a:a + n], Vr[None, :, a:a + n], "bf16")[0]
+        assert np.abs(got[s] - w).max() <= ATTN_BAR, s
+
+
 # ------------------------------------------------- seeded random shape sweep
 def test_random_shapes_whole_path(dev):
     # 40 seeded draws of (dtype, head size, batch, heads, group, length, ratio, split count): the whole

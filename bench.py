@@ -674,6 +674,21 @@ def run_uniform(cfg, dev, steps, warmup, overridden, decode_splits, copy_probe, 
             "timing": "HIP events on the launch stream around all %d calls of each step" % n_decode_launch,
         },
     }
+    # the compression step behind its single entry point, all heads at once and slab by slab
+    # (slabs of one sequence's KV heads and of one layer's), a few repetitions each
+    one_call = {}
+    for slab in (0, cfg.Hkv, cfg.B * cfg.Hkv):
+        ts = []
+        for _ in range(3):
+            a, b = ev(), ev()
+            a.record()
+            l2kv.l2kv_compress(w.K, w.V, cfg.keep_ratio, w.norms, w.idx, w.Kc, w.Vc, w.sel_ws, slab_heads=slab)
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        one_call["slab_heads_%d" % slab] = {"ms": round(float(np.median(ts)), 4),
+                                            "GBps": round(comp_bytes / float(np.median(ts)) / 1e6, 1)}
+    out["phases"]["compress_one_call"] = one_call
     if cpu_layers > 0:
         layers = list(range(min(cpu_layers, cfg.L)))
         one, many = cpu_baseline(w, layers, min(cpu_decode_steps, cfg.decode_steps), host_threads())

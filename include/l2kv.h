@@ -141,6 +141,33 @@ l2kv_status l2kv_compact(const void* K, const void* V, l2kv_dtype dt,
                          void* Kc, void* Vc, void* stream);
 
 /*
+ * The whole compression step (the rule of Sec. 1 as one operation: keep the
+ * lowest-norm keys and their values) in one call: l2kv_norms, l2kv_select and
+ * l2kv_compact enqueued back to back on `stream`, with the same results as the
+ * three separate calls.
+ *   slab_heads : 0 = all heads at once (three launches).  > 0 = the three
+ *                steps are enqueued slab by slab of that many consecutive
+ *                heads, and the norm pass reads K with ordinary instead of
+ *                non-temporal loads, so that the compaction's second read of
+ *                the kept K rows of a slab can be served by the caches while
+ *                the slab still fits them.  On an MI355X this is SLOWER than
+ *                slab_heads = 0 at the shapes measured (selection runs one
+ *                workgroup per head, so a slab of a few heads leaves most of
+ *                the chip idle during its selection); the mode exists so that
+ *                the trade can be measured.
+ *   norms      out: [n_heads][T] fp32 (needed as scratch; left filled)
+ *   kept_idx   out: [n_heads][k], k = l2kv_keep_count(T, keep_ratio)
+ *   Kc, Vc     out: [n_heads][k][D]
+ *   workspace     : as l2kv_select
+ * Errors: NULL, SHAPE, DTYPE, RATIO, WORKSPACE, ALIGN, LAUNCH (a launch failure
+ * part-way leaves the earlier slabs done).
+ */
+l2kv_status l2kv_compress(const void* K, const void* V, l2kv_dtype dt, int64_t n_heads,
+                          int64_t T, int32_t D, int64_t head_stride, double keep_ratio,
+                          int64_t slab_heads, float* norms, int32_t* kept_idx, void* Kc,
+                          void* Vc, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Decode attention (Eq. 2 for a single query row; Eq. 4: the query attends to
  * every row of the cache it is handed, the current token's row included by
  * the caller).  For each sequence b and query head hq, with KV head

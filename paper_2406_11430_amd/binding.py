@@ -33,6 +33,9 @@ SIGNATURES = {
     "l2kv_random_keys": (C.c_int, [C.c_int64, C.c_int64, C.c_uint32, C.c_void_p, C.c_void_p]),
     "l2kv_compact": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int64, C.c_int64,
                                C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "l2kv_compress": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int32, C.c_int64,
+                                C.c_double, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                C.c_void_p, C.c_size_t, C.c_void_p]),
     "l2kv_decode_attn": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32,
                                    C.c_int32, C.c_int64, C.c_int32, C.c_int64, C.c_float, C.c_void_p,
                                    C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -234,6 +237,23 @@ def l2kv_compact(K: torch.Tensor, V: Optional[torch.Tensor], kept_idx: torch.Ten
         assert V.shape == K.shape and V.dtype == K.dtype and Vc is not None and Vc.numel() == Kc.numel()
     _check("l2kv_compact", lib().l2kv_compact(_ptr(K), _ptr(V), _dtype_code(K), _ptr(kept_idx), n, T, k,
                                               D, T * D, _ptr(Kc), _ptr(Vc), _stream(stream)))
+
+
+def l2kv_compress(K: torch.Tensor, V: torch.Tensor, keep_ratio: float, norms: torch.Tensor,
+                  kept_idx: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, workspace: torch.Tensor,
+                  slab_heads: int = 0, stream=None) -> None:
+    """norms -> select -> compact in one call (optionally slab by slab of ``slab_heads`` heads)."""
+    _dev(K, V, norms, kept_idx, Kc, Vc, workspace)
+    n, T, D = _heads(K)
+    k = kept_idx.shape[-1]
+    assert V.shape == K.shape and V.dtype == K.dtype == Kc.dtype == Vc.dtype
+    assert norms.dtype == torch.float32 and norms.numel() == n * T
+    assert kept_idx.dtype == torch.int32 and kept_idx.numel() == n * k
+    assert Kc.numel() == n * k * D and Vc.numel() == n * k * D
+    _check("l2kv_compress", lib().l2kv_compress(
+        _ptr(K), _ptr(V), _dtype_code(K), n, T, D, T * D, float(keep_ratio), int(slab_heads), _ptr(norms),
+        _ptr(kept_idx), _ptr(Kc), _ptr(Vc), _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _stream(stream)))
 
 
 def l2kv_decode_attn(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, O: torch.Tensor,

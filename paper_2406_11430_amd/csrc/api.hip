@@ -68,7 +68,7 @@ l2kv_status l2kv_norms(const void* K, l2kv_dtype dt, int64_t n_heads, int64_t T,
     if (K == nullptr || norms == nullptr) return L2KV_ERR_NULL;
     if (l2kv_status st = check_cache(dt, n_heads, T, D, head_stride); st != L2KV_OK) return st;
     if (!aligned(K, 16) || !aligned(norms, 4)) return L2KV_ERR_ALIGN;
-    return norms_dispatch(K, dt, n_heads, T, D, head_stride, norms, static_cast<hipStream_t>(stream));
+    return norms_dispatch(K, dt, n_heads, T, D, head_stride, norms, false, static_cast<hipStream_t>(stream));
 }
 
 size_t l2kv_select_workspace_bytes(int64_t n_heads, int64_t T) {
@@ -115,6 +115,41 @@ l2kv_status l2kv_compact(const void* K, const void* V, l2kv_dtype dt, const int3
         return L2KV_ERR_ALIGN;
     return compact_dispatch(K, V, dt, kept_idx, n_heads, T, k, D, head_stride, Kc, Vc,
                             static_cast<hipStream_t>(stream));
+}
+
+l2kv_status l2kv_compress(const void* K, const void* V, l2kv_dtype dt, int64_t n_heads, int64_t T, int32_t D,
+                          int64_t head_stride, double keep_ratio, int64_t slab_heads, float* norms,
+                          int32_t* kept_idx, void* Kc, void* Vc, void* workspace, size_t workspace_bytes,
+                          void* stream) {
+    if (K == nullptr || V == nullptr || norms == nullptr || kept_idx == nullptr || Kc == nullptr || Vc == nullptr)
+        return L2KV_ERR_NULL;
+    if (l2kv_status st = check_cache(dt, n_heads, T, D, head_stride); st != L2KV_OK) return st;
+    if (!(keep_ratio > 0.0) || !(keep_ratio <= 1.0)) return L2KV_ERR_RATIO;
+    if (slab_heads < 0) return L2KV_ERR_SHAPE;
+    if (workspace == nullptr || workspace_bytes < l2kv_select_workspace_bytes(n_heads, T)) return L2KV_ERR_WORKSPACE;
+    if (!aligned(K, 16) || !aligned(V, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(norms, 4) ||
+        !aligned(kept_idx, 4) || !aligned(workspace, 16))
+        return L2KV_ERR_ALIGN;
+    const int64_t k = l2kv_keep_count(T, keep_ratio);
+    const int64_t slab = slab_heads == 0 || slab_heads > n_heads ? n_heads : slab_heads;
+    const bool keep_in_cache = slab < n_heads;       // the slab's K rows are read again two launches later
+    const size_t es = static_cast<size_t>(elem_bytes(dt));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int64_t h0 = 0; h0 < n_heads; h0 += slab) {
+        const int64_t nh = n_heads - h0 < slab ? n_heads - h0 : slab;
+        const char* Ks = static_cast<const char*>(K) + static_cast<size_t>(h0) * static_cast<size_t>(head_stride) * es;
+        const char* Vs = static_cast<const char*>(V) + static_cast<size_t>(h0) * static_cast<size_t>(head_stride) * es;
+        float* ns = norms + h0 * T;
+        int32_t* is = kept_idx + h0 * k;
+        const size_t dense = static_cast<size_t>(h0) * static_cast<size_t>(k) * static_cast<size_t>(D) * es;
+        l2kv_status st = norms_dispatch(Ks, dt, nh, T, D, head_stride, ns, keep_in_cache, s);
+        if (st == L2KV_OK) st = select_dispatch(ns, nh, T, k, L2KV_KEEP_LOWEST, is, nullptr, workspace, s);
+        if (st == L2KV_OK)
+            st = compact_dispatch(Ks, Vs, dt, is, nh, T, k, D, head_stride, static_cast<char*>(Kc) + dense,
+                                  static_cast<char*>(Vc) + dense, s);
+        if (st != L2KV_OK) return st;
+    }
+    return L2KV_OK;
 }
 
 int32_t l2kv_decode_max_splits(int64_t kv_len) { return decode_max_splits(kv_len); }

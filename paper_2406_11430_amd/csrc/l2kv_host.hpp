@@ -17,7 +17,7 @@ inline l2kv_status launch_status() {
 int device_compute_units();
 
 l2kv_status norms_dispatch(const void* K, l2kv_dtype dt, int64_t n_heads, int64_t T, int32_t D,
-                           int64_t head_stride, float* norms, hipStream_t stream);
+                           int64_t head_stride, float* norms, bool keep_in_cache, hipStream_t stream);
 
 l2kv_status select_dispatch(const float* norms, int64_t n_heads, int64_t T, int64_t k,
                             l2kv_mode mode, int32_t* kept_idx, int32_t* kept_count,

@@ -23,7 +23,9 @@ constexpr int kNormWaves = kNormThreads / kWaveSize;
 constexpr int kNormUnroll = L2KV_NORM_UNROLL;                    // rows per row group
 constexpr int kNormRowsPerBlock = kNormWaves * kRowsPerWaveLoad * kNormUnroll;  // 32
 
-template <typename E, int D>
+// kKeep: ordinary loads instead of non-temporal ones, for callers that read the same rows
+// again soon (the slab mode of l2kv_compress), so the rows may stay in the caches.
+template <typename E, int D, bool kKeep>
 __global__ __launch_bounds__(kNormThreads)
 void norms_kernel(const char* __restrict__ K, int64_t T, int64_t head_stride_bytes,
                   int64_t blocks_per_head, float* __restrict__ norms) {
@@ -45,7 +47,9 @@ void norms_kernel(const char* __restrict__ K, int64_t T, int64_t head_stride_byt
     for (int u = 0; u < kNormUnroll; ++u) {
         int64_t row = first + u;
         row = row < T ? row : T - 1;      // tail: re-read the last row, result unused
-        raw[u] = load_words_stream<S::kWords>(head_base + row * S::kRowBytes + c * S::kBytes);
+        const char* p = head_base + row * S::kRowBytes + c * S::kBytes;
+        if constexpr (kKeep) raw[u] = load_words<S::kWords>(p);
+        else raw[u] = load_words_stream<S::kWords>(p);
     }
 
     float mine = 0.f;
@@ -68,23 +72,24 @@ void norms_kernel(const char* __restrict__ K, int64_t T, int64_t head_stride_byt
 
 template <typename E, int D>
 static l2kv_status launch_norms(const void* K, int64_t n_heads, int64_t T, int64_t head_stride,
-                                float* norms, hipStream_t stream) {
+                                float* norms, bool keep_in_cache, hipStream_t stream) {
     const int64_t bph = (T + kNormRowsPerBlock - 1) / kNormRowsPerBlock;
     const int64_t blocks = bph * n_heads;
     if (blocks > 0x7fffffffLL) return L2KV_ERR_SHAPE;
-    hipLaunchKernelGGL((norms_kernel<E, D>), dim3((unsigned)blocks), dim3(kNormThreads), 0, stream,
+    auto kernel = keep_in_cache ? norms_kernel<E, D, true> : norms_kernel<E, D, false>;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNormThreads), 0, stream,
                        static_cast<const char*>(K), T, head_stride * (int64_t)E::kBytes, bph, norms);
     return launch_status();
 }
 
 l2kv_status norms_dispatch(const void* K, l2kv_dtype dt, int64_t n_heads, int64_t T, int32_t D,
-                           int64_t head_stride, float* norms, hipStream_t stream) {
+                           int64_t head_stride, float* norms, bool keep_in_cache, hipStream_t stream) {
     if (dt == L2KV_F32) {
-        return D == 64 ? launch_norms<F32, 64>(K, n_heads, T, head_stride, norms, stream)
-                       : launch_norms<F32, 128>(K, n_heads, T, head_stride, norms, stream);
+        return D == 64 ? launch_norms<F32, 64>(K, n_heads, T, head_stride, norms, keep_in_cache, stream)
+                       : launch_norms<F32, 128>(K, n_heads, T, head_stride, norms, keep_in_cache, stream);
     }
-    return D == 64 ? launch_norms<BF16, 64>(K, n_heads, T, head_stride, norms, stream)
-                   : launch_norms<BF16, 128>(K, n_heads, T, head_stride, norms, stream);
+    return D == 64 ? launch_norms<BF16, 64>(K, n_heads, T, head_stride, norms, keep_in_cache, stream)
+                   : launch_norms<BF16, 128>(K, n_heads, T, head_stride, norms, keep_in_cache, stream);
 }
 
 }  // namespace l2kv

@@ -122,6 +122,28 @@ def test_compact_validation(lib):
     assert f(P, P, 1, P, 1, 8, 4, 128, 1024, P, P + 8, None) == E_ALIGN
 
 
+def test_compress_validation(lib):
+    f = lib.l2kv_compress
+    ok = [P, P, 1, 4, 1000, 128, 128000, 0.5, 0, P, P, P, P, P, 256, None]
+    names = ["K", "V", "dt", "n_heads", "T", "D", "stride", "ratio", "slab", "norms", "idx", "Kc", "Vc", "ws",
+             "ws_bytes", "stream"]
+
+    def call(**kw):
+        args = list(ok)
+        for key, val in kw.items():
+            args[names.index(key)] = val
+        return f(*args)
+
+    for key in ("K", "V", "norms", "idx", "Kc", "Vc"):
+        assert call(**{key: None}) == E_NULL
+    assert call(dt=3) == E_DTYPE
+    assert call(n_heads=0) == E_SHAPE and call(T=0) == E_SHAPE and call(D=96) == E_SHAPE
+    assert call(stride=127999) == E_SHAPE and call(slab=-1) == E_SHAPE
+    assert call(ratio=0.0) == E_RATIO and call(ratio=1.5) == E_RATIO and call(ratio=float("nan")) == E_RATIO
+    assert call(ws=None) == E_WS and call(ws_bytes=8) == E_WS
+    assert call(K=P + 2) == E_ALIGN and call(Vc=P + 8) == E_ALIGN and call(ws=P + 4) == E_ALIGN
+
+
 def test_decode_validation(lib):
     f = lib.l2kv_decode_attn
     ws = lib.l2kv_decode_workspace_bytes(2, 8, 100, 128)

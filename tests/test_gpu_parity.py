@@ -487,6 +487,28 @@ def test_kept_set_ignores_values_on_gpu(dev):
         assert set(perm[c[0, 0].cpu()].tolist()) == set(a[0, 0].cpu().tolist())
 
 
+@pytest.mark.parametrize("slab", [0, 1, 3, 100])
+def test_compress_in_one_call(dev, slab):
+    # norms -> select -> compact behind one entry point, all heads at once or slab by slab (7 heads
+    # in slabs of 3 leave a last slab of one): identical to the oracle in every mode
+    rng = np.random.default_rng(41)
+    n_heads, T, D, r = 7, 1801, 128, 0.37
+    K, V = rand_cache(rng, (n_heads, T, D), "bf16"), rand_cache(rng, (n_heads, T, D), "bf16")
+    K[:, ::6] = K[:, :1]                                             # ties in the norms
+    k = oracle.keep_count(T, r)
+    Kd, Vd = to_dev(K, "bf16", dev), to_dev(V, "bf16", dev)
+    norms = torch.full((n_heads, T), -1.0, dtype=torch.float32, device=dev)
+    idx = torch.full((n_heads, k), -1, dtype=torch.int32, device=dev)
+    Kc = torch.zeros((n_heads, k, D), dtype=torch.bfloat16, device=dev)
+    Vc = torch.zeros_like(Kc)
+    ws = torch.empty(l2kv.l2kv_select_workspace_bytes(n_heads, T), dtype=torch.uint8, device=dev)
+    l2kv.l2kv_compress(Kd, Vd, r, norms, idx, Kc, Vc, ws, slab_heads=slab)
+    n32, _, want_idx, want_K, want_V = oracle.compress(K, V, "bf16", r)
+    assert np.array_equal(norms.cpu().numpy().view(np.uint32), n32.view(np.uint32))
+    assert np.array_equal(idx.cpu().numpy(), want_idx)
+    assert np.array_equal(synth.as_numpy_bits(Kc), want_K) and np.array_equal(synth.as_numpy_bits(Vc), want_V)
+
+
 # ------------------------------------------------- control strategies of Sec. 4
 def test_keep_random_control_matches_oracle(dev):
     n_heads, T, k, seed = 6, 3000, 1000, 20240611

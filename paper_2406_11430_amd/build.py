@@ -67,5 +67,24 @@ def build_library(extra_flags=(), jobs: int = 8, out: str = LIB_PATH, obj_dir: s
     return out
 
 
+C_DRIVER_SRC = os.path.join(os.path.dirname(HERE), "tests", "abi_c", "l2kv_c_driver.c")
+C_DRIVER_BIN = os.path.join(os.path.dirname(HERE), "tests", "abi_c", "l2kv_c_driver")
+
+
+def build_c_driver() -> str:
+    """Compile the plain-C program that drives the library with hipMalloc memory (gcc, C99) and
+    link it against libl2kv.so and the HIP runtime.  Needs the library built first."""
+    rocm = os.path.dirname(os.path.dirname(hipcc()))
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I" + os.path.join(rocm, "include"),
+           "-I" + os.path.join(os.path.dirname(HERE), "include"), C_DRIVER_SRC, "-o", C_DRIVER_BIN,
+           "-L" + HERE, "-ll2kv", "-L" + os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../../paper_2406_11430_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("gcc failed for the C driver:\n" + res.stderr)
+    return C_DRIVER_BIN
+
+
 if __name__ == "__main__":
     print(build_library(sys.argv[1:]))
+    print(build_c_driver())

@@ -203,6 +203,16 @@ l2kv_status l2kv_decode_attn(const void* Q, const void* Kc, const void* Vc,
                              float scale, float* O, void* workspace,
                              size_t workspace_bytes, void* stream);
 
+/* Same with the element type of O chosen by the caller: L2KV_F32 (O is float*,
+ * identical to l2kv_decode_attn) or L2KV_BF16 (O is [B][Hq][D] bf16, 2-byte
+ * aligned: the fp32 result rounded to nearest even once, at the very end).
+ * Errors: as l2kv_decode_attn; DTYPE also for an unknown out_dt. */
+l2kv_status l2kv_decode_attn_out(const void* Q, const void* Kc, const void* Vc,
+                                 l2kv_dtype dt, int32_t B, int32_t Hq, int32_t Hkv,
+                                 int64_t kv_len, int32_t D, int64_t kv_head_stride,
+                                 float scale, l2kv_dtype out_dt, void* O, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+
 /* Same with the number of row ranges per KV head chosen by the caller
  * (1 <= n_splits <= l2kv_decode_max_splits(kv_len); 0 = library default).
  * The result does not depend on n_splits beyond fp32 rounding. */

@@ -39,6 +39,9 @@ SIGNATURES = {
     "l2kv_decode_attn": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32,
                                    C.c_int32, C.c_int64, C.c_int32, C.c_int64, C.c_float, C.c_void_p,
                                    C.c_void_p, C.c_size_t, C.c_void_p]),
+    "l2kv_decode_attn_out": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int32, C.c_int32,
+                                       C.c_int32, C.c_int64, C.c_int32, C.c_int64, C.c_float, C.c_int,
+                                       C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "l2kv_decode_attn_splits": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int32,
                                           C.c_int32, C.c_int32, C.c_int64, C.c_int32, C.c_int64,
                                           C.c_float, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
@@ -281,6 +284,19 @@ def l2kv_decode_attn_splits(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor,
                                            D, n * D, float(scale), int(n_splits), _ptr(O),
                                            _ptr(workspace), ws_bytes, _stream(stream))
         _check("l2kv_decode_attn_splits", st)
+
+
+def l2kv_decode_attn_out(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, O: torch.Tensor,
+                         workspace: torch.Tensor, scale: float = 0.0, stream=None) -> None:
+    """l2kv_decode_attn with O ``[B, Hq, D]`` in float32 or bfloat16 (the tensor's dtype decides)."""
+    _dev(Q, Kc, Vc, O, workspace)
+    B, Hq, D = Q.shape
+    Bk, Hkv, n, Dk = Kc.shape
+    assert (Bk, Dk) == (B, D) and Vc.shape == Kc.shape and Kc.dtype == Q.dtype == Vc.dtype
+    assert O.numel() == B * Hq * D
+    _check("l2kv_decode_attn_out", lib().l2kv_decode_attn_out(
+        _ptr(Q), _ptr(Kc), _ptr(Vc), _dtype_code(Q), B, Hq, Hkv, n, D, n * D, float(scale), _dtype_code(O),
+        _ptr(O), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def l2kv_decode_attn_static(Q: torch.Tensor, Kc: torch.Tensor, Vc: torch.Tensor, O: torch.Tensor,

@@ -174,7 +174,7 @@ size_t l2kv_decode_workspace_bytes(int32_t B, int32_t Hq, int64_t kv_len, int32_
 // Argument checks shared by the uniform decode entry points (everything but the workspace).
 static l2kv_status check_decode(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt, int32_t B,
                                 int32_t Hq, int32_t Hkv, int64_t kv_len, int32_t D, int64_t kv_head_stride,
-                                float scale, int32_t n_splits, const float* O) {
+                                float scale, int32_t n_splits, const void* O, uintptr_t o_align = 4) {
     if (Q == nullptr || Kc == nullptr || Vc == nullptr || O == nullptr) return L2KV_ERR_NULL;
     if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || kv_len <= 0 || kv_len > kMaxTokens || !dim_ok(D))
@@ -186,7 +186,7 @@ static l2kv_status check_decode(const void* Q, const void* Kc, const void* Vc, l
     if (n_splits < 0 || n_splits > decode_max_splits(kv_len)) return L2KV_ERR_SHAPE;
     if (!std::isfinite(scale)) return L2KV_ERR_SHAPE;
     if ((kv_head_stride * elem_bytes(dt)) % 16 != 0) return L2KV_ERR_ALIGN;
-    if (!aligned(Q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(O, 4)) return L2KV_ERR_ALIGN;
+    if (!aligned(Q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(O, o_align)) return L2KV_ERR_ALIGN;
     return L2KV_OK;
 }
 
@@ -206,6 +206,25 @@ l2kv_status l2kv_decode_attn_splits(const void* Q, const void* Kc, const void* V
     const DecodePlan plan = decode_plan(B, Hkv, Hq / Hkv, kv_len, n_splits);
     return decode_dispatch(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, nullptr, nullptr, nullptr, s,
                            plan, O, workspace, static_cast<hipStream_t>(stream));
+}
+
+l2kv_status l2kv_decode_attn_out(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt, int32_t B,
+                                 int32_t Hq, int32_t Hkv, int64_t kv_len, int32_t D, int64_t kv_head_stride,
+                                 float scale, l2kv_dtype out_dt, void* O, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+    if (O != nullptr && !dtype_ok(out_dt)) return L2KV_ERR_DTYPE;
+    l2kv_status st = check_decode(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, scale, 0, O,
+                                  out_dt == L2KV_BF16 ? 2 : 4);
+    if (st != L2KV_OK && st != L2KV_ERR_ALIGN) return st;
+    if (workspace == nullptr || workspace_bytes < l2kv_decode_workspace_bytes(B, Hq, kv_len, D))
+        return L2KV_ERR_WORKSPACE;
+    if (st != L2KV_OK) return st;
+    if (!aligned(workspace, 16)) return L2KV_ERR_ALIGN;
+    const float s = scale > 0.f ? scale : 1.0f / std::sqrt(static_cast<float>(D));
+    DecodePlan plan = decode_plan(B, Hkv, Hq / Hkv, kv_len, 0);
+    plan.out_bf16 = out_dt == L2KV_BF16 ? 1 : 0;
+    return decode_dispatch(Q, Kc, Vc, dt, B, Hq, Hkv, kv_len, D, kv_head_stride, nullptr, nullptr, nullptr, s,
+                           plan, static_cast<float*>(O), workspace, static_cast<hipStream_t>(stream));
 }
 
 l2kv_status l2kv_decode_attn_static(const void* Q, const void* Kc, const void* Vc, l2kv_dtype dt,

@@ -120,6 +120,7 @@ DecodePlan decode_plan(int32_t B, int32_t Hkv, int32_t group, int64_t kv_len, in
     plan.n_splits = (int32_t)want;
     plan.rows_per_wg = 1;
     plan.worklist_wgs = 0;
+    plan.out_bf16 = 0;
     return plan;
 }
 
@@ -130,6 +131,7 @@ DecodePlan decode_plan_ragged(int32_t n_seq, int32_t Hkv, int64_t max_len, int32
     const int64_t cap = decode_max_splits(max_len);
     DecodePlan plan;
     plan.worklist_wgs = 0;
+    plan.out_bf16 = 0;
     if (ordered && max_len >= kOrderedMinRows) {
         // A longest-first order is known.  One item of the work list is a whole
         // (sequence, KV head) -- only sequences beyond 16k rows, or all of them

@@ -78,6 +78,18 @@ __device__ __forceinline__ f32x4 fetch4(__amdgpu_buffer_rsrc_t region, int byte_
     return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(region, byte_offset, 0, kCachePolicySc1));
 }
 
+// One output element: fp32, or bf16 (round to nearest even) when the caller asked for it; O then
+// points at 16-bit elements.
+__device__ __forceinline__ void store_out(float* O, int64_t i, float v, int out_bf16) {
+    if (out_bf16) {
+        const uint32_t u = __builtin_bit_cast(uint32_t, v);
+        const uint32_t r = (u & 0x7f800000u) == 0x7f800000u ? u : u + 0x7fffu + ((u >> 16) & 1u);   // Inf / NaN: truncate
+        reinterpret_cast<uint16_t*>(O)[i] = (uint16_t)(r >> 16);
+    } else {
+        O[i] = v;
+    }
+}
+
 template <typename E, int D>
 struct Tile {
     Words<Slice<E, D>::kWords> k[kDecLoads];
@@ -133,7 +145,7 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
                                             const char* __restrict__ Vh, int64_t kv_len, int64_t hq0,
                                             int split, int n_splits, int n_splits_grid,
                                             float scale_log2e, uint32_t* __restrict__ counter,
-                                            float* __restrict__ partial, float* __restrict__ O,
+                                            float* __restrict__ partial, float* __restrict__ O, int out_bf16,
                                             uint32_t* __restrict__ queue, uint32_t& drawn) {
     using S = Slice<E, D>;
     constexpr int EPL = S::kElems;
@@ -345,7 +357,7 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
         }
         if (n_splits == 1) {
             // the only workgroup of this KV head: its merge is the result (0 for an empty cache)
-            O[hq0 * D + o] = den > 0.f ? num / den : 0.f;
+            store_out(O, hq0 * D + o, den > 0.f ? num / den : 0.f, out_bf16);
         } else {
             // Device-scope stores: written through to the level every compute unit
             // of the device reads from, so the merging workgroup below sees them
@@ -422,7 +434,7 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
                 }
             }
             const int o = threadIdx.x + j * kDecThreads;
-            if (o < G * D) O[hq0 * D + o] = den > 0.f ? num / den : 0.f;   // 0 for an empty cache
+            if (o < G * D) store_out(O, hq0 * D + o, den > 0.f ? num / den : 0.f, out_bf16);   // 0 for an empty cache
         }
     } else {
     // Launches with more than 8 workgroups per KV head: final merge in one memory round trip.  The weights depend on (m, l) only,
@@ -535,7 +547,7 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
 #pragma unroll
                 for (int i = 0; i < 8; ++i) den += i0 + i < n_splits ? r[i] : 0.f;
             }
-            O[hq0 * D + o] = den > 0.f ? num / den : 0.f;                 // 0 for an empty cache
+            store_out(O, hq0 * D + o, den > 0.f ? num / den : 0.f, out_bf16);   // 0 for an empty cache
         }
     }
     }
@@ -554,7 +566,7 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
                    const int64_t* __restrict__ slot_off, const int32_t* __restrict__ seq_order,
                    int n_splits_grid, int rows_per_wg,
                    float scale_log2e, uint32_t* __restrict__ counters,
-                   float* __restrict__ partial, float* __restrict__ O) {
+                   float* __restrict__ partial, float* __restrict__ O, int out_bf16) {
     using S = Slice<E, D>;
     const int split = blockIdx.x;
     const int pair = blockIdx.y;                 // b * Hkv + hkv
@@ -592,7 +604,7 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
     }
     uint32_t unused = 0;
     decode_item<E, D, G, kWideMerge>(Q, Kc + slab, Vc + slab, kv_len, hq0, split, n_splits, n_splits_grid,
-                                     scale_log2e, counters + ((int64_t)b * Hkv + hkv), partial, O, nullptr, unused);
+                                     scale_log2e, counters + ((int64_t)b * Hkv + hkv), partial, O, out_bf16, nullptr, unused);
 }
 
 // Work-list launch for ragged batches with a known longest-first order.  A
@@ -613,7 +625,7 @@ void decode_worklist_kernel(const char* __restrict__ Q, const char* __restrict__
                             const int32_t* __restrict__ lens, const int64_t* __restrict__ slot_off,
                             const int32_t* __restrict__ seq_order, int n_splits_grid, int rows_per_wg,
                             float scale_log2e, uint32_t* __restrict__ counters, uint32_t* __restrict__ queue,
-                            float* __restrict__ partial, float* __restrict__ O) {
+                            float* __restrict__ partial, float* __restrict__ O, int out_bf16) {
     using S = Slice<E, D>;
     __shared__ uint32_t s_item;
     const uint32_t n_items = (uint32_t)n_seq * (uint32_t)Hkv * (uint32_t)n_splits_grid;
@@ -646,7 +658,7 @@ void decode_worklist_kernel(const char* __restrict__ Q, const char* __restrict__
         }
         const int64_t hq0 = (int64_t)b * Hq + (int64_t)hkv * G;
         decode_item<E, D, G, kWideMerge>(Q, Kc + slab, Vc + slab, kv_len, hq0, split, n_splits, n_splits_grid,
-                                         scale_log2e, counters + ((int64_t)b * Hkv + hkv), partial, O, &queue[0], drawn);
+                                         scale_log2e, counters + ((int64_t)b * Hkv + hkv), partial, O, out_bf16, &queue[0], drawn);
     }
     if (threadIdx.x == 0) {
         // every draw of this workgroup has returned (its value was used above), so the workgroup
@@ -679,7 +691,7 @@ l2kv_status launch_decode(const void* Q, const void* Kc, const void* Vc, int32_t
                            dim3(kDecThreads), 0, stream, static_cast<const char*>(Q),
                            static_cast<const char*>(Kc), static_cast<const char*>(Vc), (int)Hkv, (int)B,
                            kv_head_stride * (int64_t)E::kBytes, lens, slot_off, seq_order,
-                           (int)plan.n_splits, (int)plan.rows_per_wg, scale_log2e, counters, queue, partial, O);
+                           (int)plan.n_splits, (int)plan.rows_per_wg, scale_log2e, counters, queue, partial, O, (int)plan.out_bf16);
         return launch_status();
     }
     dim3 grid((unsigned)plan.n_splits, (unsigned)(B * Hkv));
@@ -688,7 +700,7 @@ l2kv_status launch_decode(const void* Q, const void* Kc, const void* Vc, int32_t
                        static_cast<const char*>(Q), static_cast<const char*>(Kc),
                        static_cast<const char*>(Vc), (int)Hkv, kv_len,
                        kv_head_stride * (int64_t)E::kBytes, lens, slot_off, seq_order, (int)plan.n_splits,
-                       (int)plan.rows_per_wg, scale_log2e, counters, partial, O);
+                       (int)plan.rows_per_wg, scale_log2e, counters, partial, O, (int)plan.out_bf16);
     return launch_status();
 }
 

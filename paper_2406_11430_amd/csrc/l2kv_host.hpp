@@ -35,6 +35,7 @@ struct DecodePlan {
     int32_t n_splits;        // workgroups launched per KV head
     int32_t rows_per_wg;     // ragged batches: a sequence of n rows employs ceil(n / rows_per_wg) of them
     int32_t worklist_wgs;    // > 0: ordered ragged batch, this many workgroups draw items from a device-side list
+    int32_t out_bf16;        // 1: O is written as bf16 (16-bit elements behind the float pointer), 0: fp32
 };
 constexpr int kDecodeMaxSplits = 256;
 constexpr int kDecodeRowTile = 64;   // rows one workgroup consumes per step (4 waves x 16)

@@ -174,6 +174,29 @@ def test_decode_validation(lib):
     assert g(P, P, P, 1, 2, 8, 2, 100, 128, 12800, 0.0, -1, P, P, ws, None) == E_SHAPE
 
 
+def test_decode_out_validation(lib):
+    f = lib.l2kv_decode_attn_out
+    ws = lib.l2kv_decode_workspace_bytes(2, 8, 100, 128)
+    ok = (P, P, P, 1, 2, 8, 2, 100, 128, 12800, 0.0, 1, P, P, ws, None)
+    names = ["Q", "Kc", "Vc", "dt", "B", "Hq", "Hkv", "kv_len", "D", "stride", "scale", "out_dt", "O", "ws",
+             "ws_bytes", "stream"]
+
+    def call(**kw):
+        args = list(ok)
+        for key, val in kw.items():
+            args[names.index(key)] = val
+        return f(*args)
+
+    for key in ("Q", "Kc", "Vc", "O"):
+        assert call(**{key: None}) == E_NULL
+    assert call(out_dt=7) == E_DTYPE and call(dt=9) == E_DTYPE
+    assert call(Hq=18) == E_SHAPE and call(kv_len=-1) == E_SHAPE
+    assert call(ws=None) == E_WS and call(ws_bytes=ws - 16) == E_WS
+    assert call(O=P + 2, out_dt=0) == E_ALIGN          # fp32 output needs 4-byte alignment
+    assert call(O=P + 1) == E_ALIGN                     # bf16 output needs 2
+    assert call(Q=P + 8) == E_ALIGN
+
+
 def test_decode_static_validation(lib):
     f = lib.l2kv_decode_attn_static
     ok = (P, P, P, 1, 2, 8, 2, 100, 128, 12800, 0.0, P, None)

@@ -291,6 +291,30 @@ def test_decode_closed_forms_on_gpu(dev):
     assert np.abs(c.cpu().numpy() - oracle.decode_attn(Q, K, V, dt, scale=0.3)).max() <= ATTN_BAR
 
 
+@pytest.mark.parametrize("B,Hkv,G,n", [(2, 2, 4, 3000), (1, 8, 4, 13108), (3, 1, 1, 70)])
+def test_decode_bf16_output(dev, B, Hkv, G, n):
+    # the optional bf16 output is the fp32 result rounded to nearest even once at the very end:
+    # bit-identical to rounding the fp32 output of the plain call, and within half a bf16 unit in
+    # the last place (plus the fp32 bar) of the oracle
+    rng = np.random.default_rng(n)
+    D = 128
+    K, V = rand_cache(rng, (B, Hkv, n, D), "bf16"), rand_cache(rng, (B, Hkv, n, D), "bf16")
+    Q = rand_cache(rng, (B, Hkv * G, D), "bf16")
+    Qd, Kd, Vd = (to_dev(a, "bf16", dev) for a in (Q, K, V))
+    ws = torch.zeros(l2kv.l2kv_decode_workspace_bytes(B, Hkv * G, n, D), dtype=torch.uint8, device=dev)
+    O32 = torch.empty((B, Hkv * G, D), dtype=torch.float32, device=dev)
+    O16 = torch.full((B, Hkv * G, D), float("nan"), dtype=torch.bfloat16, device=dev)
+    O32b = torch.empty_like(O32)
+    l2kv.l2kv_decode_attn(Qd, Kd, Vd, O32, ws)
+    l2kv.l2kv_decode_attn_out(Qd, Kd, Vd, O16, ws)
+    l2kv.l2kv_decode_attn_out(Qd, Kd, Vd, O32b, ws)
+    assert torch.equal(O32.view(torch.int32), O32b.view(torch.int32))
+    assert torch.equal(O16.view(torch.int16), O32.to(torch.bfloat16).view(torch.int16))   # torch rounds to nearest even
+    want = oracle.decode_attn(Q, K, V, "bf16")
+    err = np.abs(O16.float().cpu().numpy() - want)
+    assert np.all(err <= ATTN_BAR + np.abs(want) * 2.0 ** -8)
+
+
 def test_decode_workspace_init_entry_point(dev):
     # a workspace full of garbage, cleared by the library's own fill kernel, then reused
     rng = np.random.default_rng(44)

@@ -46,7 +46,7 @@ HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak (8 TB/s): the figure e
 # plain 1 GiB copy in the same runs): profiles/hot_path_hbm_traffic_pmc.md.
 # A constant from that offline profile, not something this run measures;
 # reported only when the timed shape is that shape.
-PROFILED_DECODE_TRAFFIC_BYTES = {("bf16", 4, 8, 32, 128, 16384): (263036 + 539) * 1024}
+PROFILED_DECODE_TRAFFIC_BYTES = {("bf16", 4, 8, 32, 128, 16384): (263059 + 527) * 1024}
 
 
 def host_threads():
@@ -539,6 +539,12 @@ def main():
     ap.add_argument("--no-seq-order", action="store_true",
                     help="streaming workloads: pass no stored launch order to the ragged attention calls "
                          "(the library then works one out per call; for comparisons)")
+    ap.add_argument("--q-heads", type=int, default=0,
+                    help="override the number of query heads (a multiple of the KV heads): other query-group "
+                         "sizes at the workload's shape, for profiles")
+    ap.add_argument("--one-call-slabs", default=None,
+                    help="comma-separated slab sizes (heads; 0 = all at once) for the l2kv_compress timings; "
+                         "'none' skips them (default: 0, one sequence's KV heads, one layer's heads)")
     ap.add_argument("--no-other-workloads", action="store_true",
                     help="default C3 run only: skip the short C4 and C5 passes reported under other_workloads")
     ap.add_argument("--alr", action="store_true",
@@ -569,8 +575,13 @@ def main():
         cfg, overridden = cfg.scaled(L=args.layers), True
     if args.decode_steps:
         cfg, overridden = cfg.scaled(decode_steps=args.decode_steps), True
+    if args.q_heads:
+        cfg, overridden = cfg.scaled(Hq=args.q_heads), True
+    slabs = None
+    if args.one_call_slabs is not None:
+        slabs = [] if args.one_call_slabs == "none" else [int(x) for x in args.one_call_slabs.split(",")]
     out = run_uniform(cfg, dev, args.steps, args.warmup, overridden, args.decode_splits, args.copy_probe,
-                      0 if args.no_cpu_baseline else args.cpu_layers, args.cpu_decode_steps)
+                      0 if args.no_cpu_baseline else args.cpu_layers, args.cpu_decode_steps, slabs)
     out["device"] = device_facts(dev)
     if args.workload == "C3" and not overridden and not args.no_other_workloads:
         # one short pass each of the other two full-size workloads, same fields, so that their
@@ -582,7 +593,8 @@ def main():
     print(json.dumps(out))
 
 
-def run_uniform(cfg, dev, steps, warmup, overridden, decode_splits, copy_probe, cpu_layers, cpu_decode_steps):
+def run_uniform(cfg, dev, steps, warmup, overridden, decode_splits, copy_probe, cpu_layers, cpu_decode_steps,
+                one_call_slabs=None):
     w = Workload(cfg, dev, decode_splits)
     k = w.k
     nb, sb, cb = compress_bytes_per_layer(cfg, k)
@@ -677,7 +689,7 @@ def run_uniform(cfg, dev, steps, warmup, overridden, decode_splits, copy_probe, 
     # the compression step behind its single entry point, all heads at once and slab by slab
     # (slabs of one sequence's KV heads and of one layer's), a few repetitions each
     one_call = {}
-    for slab in (0, cfg.Hkv, cfg.B * cfg.Hkv):
+    for slab in ((0, cfg.Hkv, cfg.B * cfg.Hkv) if one_call_slabs is None else one_call_slabs):
         ts = []
         for _ in range(3):
             a, b = ev(), ev()

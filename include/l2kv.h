@@ -304,7 +304,8 @@ l2kv_status l2kv_select_ragged(const float* norms, int32_t n_planes, int32_t n_s
  * row kept_idx[..][j] of that sequence (K, V, its norm, and the position as
  * token id).  Sets up the cache that l2kv_stream_* and l2kv_decode_attn_ragged
  * work on; lens[s] = k_s is the caller's to fill.  k_s is capped at the
- * sequence's slot capacity.  max_kept: an upper bound of all k_s.
+ * sequence's slot capacity.  max_kept: an upper bound of all k_s (checked against
+ * total_kept; the launch itself is sized by total_kept).
  * Errors: NULL, SHAPE, DTYPE, ALIGN, LAUNCH.
  */
 l2kv_status l2kv_compact_ragged(const void* K, const void* V, const float* norms, l2kv_dtype dt,

@@ -30,63 +30,82 @@ constexpr int kRagWaves = kRagThreads / kWaveSize;
 constexpr int kRagUnroll = 4;
 constexpr int kRagRowsPerBlock = kRagWaves * kRowsPerWaveLoad * kRagUnroll;   // 64
 
-// grid.x = blocks_per_seq * n_seq * n_planes (block -> (plane, seq, chunk of 64 kept rows))
+// Index of the sequence whose output range holds flat kept row j of a plane: the last s in
+// [0, n_seq) with out_off[s] <= j (binary search; offsets ascend in a consistent batch, and
+// whatever they hold the result is a valid sequence index).
+__device__ __forceinline__ int64_t owner_of_row(const int64_t* __restrict__ out_off, int64_t n_seq, int64_t j) {
+    int64_t lo = 0, hi = n_seq - 1;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) >> 1;
+        if (out_off[mid] <= j) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// grid.x = chunks_per_plane * n_planes: the kept rows of a plane, all sequences back to back
+// (as kept_idx holds them), are cut into chunks of 64 consecutive rows, so every workgroup has
+// a full chunk whatever the lengths of the sequences are (a launch sized by the longest
+// sequence would leave almost half of its workgroups without work on a batch of mixed lengths).
+// A row group takes 4 consecutive flat rows, which may belong to different sequences.
 template <int W>
 __global__ __launch_bounds__(kRagThreads)
 void compact_ragged_kernel(const char* __restrict__ K, const char* __restrict__ V,
                            const float* __restrict__ norms, const int32_t* __restrict__ kept_idx,
                            int64_t n_seq, int64_t total_tokens, const int64_t* __restrict__ in_off,
                            const int64_t* __restrict__ out_off, int64_t total_kept,
-                           int64_t blocks_per_seq, const int64_t* __restrict__ slot_off,
+                           int64_t chunks_per_plane, const int64_t* __restrict__ slot_off,
                            int64_t total_slots, char* __restrict__ Kc, char* __restrict__ Vc,
                            float* __restrict__ norms_c, int32_t* __restrict__ pos_c) {
     constexpr int64_t kSliceBytes = 4 * W;
     constexpr int64_t kRowBytes = kRowLanes * kSliceBytes;
-    const int64_t chunk = blockIdx.x % blocks_per_seq;
-    const int64_t seq = (blockIdx.x / blocks_per_seq) % n_seq;
-    const int64_t plane = blockIdx.x / (blocks_per_seq * n_seq);
+    const int64_t chunk = blockIdx.x % chunks_per_plane;
+    const int64_t plane = blockIdx.x / chunks_per_plane;
     const int lane = threadIdx.x % kWaveSize;
     const int wave = threadIdx.x / kWaveSize;
     const int c = lane % kRowLanes;
     const int rg = lane / kRowLanes;
 
-    const Range in = clamped_range(in_off, seq, total_tokens);
-    const Range outr = clamped_range(out_off, seq, total_kept);
-    const Range slots = clamped_range(slot_off, seq, total_slots);
-    const int64_t T = in.count;
-    const int64_t k = outr.count < slots.count ? outr.count : slots.count;   // never write past the sequence's slots
     const int64_t first = chunk * kRagRowsPerBlock + (wave * kRowsPerWaveLoad + rg) * kRagUnroll;
-    if (first >= k || T <= 0) return;
+    if (first >= total_kept) return;
+    const int32_t* idx = kept_idx + plane * total_kept;
 
-    const int32_t* idx = kept_idx + plane * total_kept + outr.first;
-    const int64_t src_seq = plane * total_tokens + in.first;        // rows
-    const int64_t dst_seq = plane * total_slots + slots.first;      // slots
-
+    // per row: its sequence, source row and destination slot; a row that the (possibly
+    // inconsistent) offset arrays do not place inside its sequence's ranges is skipped
+    int64_t src[kRagUnroll], dst[kRagUnroll];
     int32_t tok[kRagUnroll];
+    bool live[kRagUnroll];
+    int64_t seq = owner_of_row(out_off, n_seq, first);
 #pragma unroll
     for (int u = 0; u < kRagUnroll; ++u) {
-        const int64_t j = first + u < k ? first + u : k - 1;
+        const int64_t j = first + u < total_kept ? first + u : total_kept - 1;
+        while (seq + 1 < n_seq && out_off[seq + 1] <= j) ++seq;
+        const Range in = clamped_range(in_off, seq, total_tokens);
+        const Range outr = clamped_range(out_off, seq, total_kept);
+        const Range slots = clamped_range(slot_off, seq, total_slots);
+        const int64_t k = outr.count < slots.count ? outr.count : slots.count;   // never write past the sequence's slots
+        const int64_t local = j - outr.first;
+        live[u] = first + u < total_kept && local >= 0 && local < k && in.count > 0;
         int32_t t = idx[j];
+        const int64_t T = in.count > 0 ? in.count : 1;
         t = t < 0 ? 0 : (t < T ? t : (int32_t)(T - 1));      // stay inside the sequence whatever idx holds
         tok[u] = t;
+        // a skipped row still gets an in-bounds source (row 0 of the plane) so the loads below need no branch
+        src[u] = plane * total_tokens + (live[u] ? in.first + t : 0);
+        dst[u] = plane * total_slots + slots.first + (live[u] ? local : 0);
     }
     Words<W> kr[kRagUnroll], vr[kRagUnroll];
 #pragma unroll
-    for (int u = 0; u < kRagUnroll; ++u)
-        kr[u] = load_words_stream<W>(K + (src_seq + tok[u]) * kRowBytes + c * kSliceBytes);
+    for (int u = 0; u < kRagUnroll; ++u) kr[u] = load_words_stream<W>(K + src[u] * kRowBytes + c * kSliceBytes);
 #pragma unroll
-    for (int u = 0; u < kRagUnroll; ++u)
-        vr[u] = load_words_stream<W>(V + (src_seq + tok[u]) * kRowBytes + c * kSliceBytes);
+    for (int u = 0; u < kRagUnroll; ++u) vr[u] = load_words_stream<W>(V + src[u] * kRowBytes + c * kSliceBytes);
 #pragma unroll
     for (int u = 0; u < kRagUnroll; ++u) {
-        const int64_t j = first + u;
-        if (j < k) {
-            const int64_t slot = dst_seq + j;
-            store_words_stream<W>(Kc + slot * kRowBytes + c * kSliceBytes, kr[u]);
-            store_words_stream<W>(Vc + slot * kRowBytes + c * kSliceBytes, vr[u]);
+        if (live[u]) {
+            store_words_stream<W>(Kc + dst[u] * kRowBytes + c * kSliceBytes, kr[u]);
+            store_words_stream<W>(Vc + dst[u] * kRowBytes + c * kSliceBytes, vr[u]);
             if (c == 0) {
-                norms_c[slot] = norms[src_seq + tok[u]];
-                pos_c[slot] = tok[u];
+                norms_c[dst[u]] = norms[src[u]];
+                pos_c[dst[u]] = tok[u];
             }
         }
     }
@@ -98,14 +117,15 @@ l2kv_status compact_ragged_dispatch(const void* K, const void* V, const float* n
                                     int64_t total_kept, int64_t max_kept, const int64_t* slot_off,
                                     int64_t total_slots, int32_t D, void* Kc, void* Vc, float* norms_c,
                                     int32_t* pos_c, hipStream_t stream) {
+    (void)max_kept;                                    // the launch is sized by total_kept
     const int row_bytes = D * (dt == L2KV_F32 ? 4 : 2);
-    const int64_t bps = (max_kept + kRagRowsPerBlock - 1) / kRagRowsPerBlock;
-    const int64_t blocks = bps * n_seq * n_planes;
+    const int64_t cpp = (total_kept + kRagRowsPerBlock - 1) / kRagRowsPerBlock;
+    const int64_t blocks = cpp * n_planes;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return L2KV_ERR_SHAPE;
 #define L2KV_RAG(WW)                                                                               \
     hipLaunchKernelGGL((compact_ragged_kernel<WW>), dim3((unsigned)blocks), dim3(kRagThreads), 0,  \
                        stream, static_cast<const char*>(K), static_cast<const char*>(V), norms,   \
-                       kept_idx, (int64_t)n_seq, total_tokens, in_off, out_off, total_kept, bps,   \
+                       kept_idx, (int64_t)n_seq, total_tokens, in_off, out_off, total_kept, cpp,   \
                        slot_off, total_slots, static_cast<char*>(Kc), static_cast<char*>(Vc),      \
                        norms_c, pos_c)
     switch (row_bytes) {
@@ -228,11 +248,26 @@ void stream_evict_kernel(int64_t n_seq, const int64_t* __restrict__ slot_off, in
     while (len > budget) {                         // uniform over the workgroup
         unsigned long long best = 0;
         int32_t best_slot = -1;
-        for (int32_t j = threadIdx.x; j < len; j += kEvictThreads) {
-            const unsigned long long key = ((unsigned long long)nb[j] << 32) | (uint32_t)pw[j];
-            if (best_slot < 0 || key > best) {
-                best = key;
-                best_slot = j;
+        // four slots per lane and step, their eight loads issued before the first compare
+        // (positions past the end re-read the last slot, which cannot beat itself)
+        constexpr int kScan = 4;
+        for (int32_t j0 = threadIdx.x; j0 < len; j0 += kScan * kEvictThreads) {
+            uint32_t nv[kScan];
+            int32_t pv[kScan], js[kScan];
+#pragma unroll
+            for (int u = 0; u < kScan; ++u) {
+                const int32_t j = j0 + u * kEvictThreads;
+                js[u] = j < len ? j : len - 1;
+                nv[u] = nb[js[u]];
+                pv[u] = pw[js[u]];
+            }
+#pragma unroll
+            for (int u = 0; u < kScan; ++u) {
+                const unsigned long long key = ((unsigned long long)nv[u] << 32) | (uint32_t)pv[u];
+                if (best_slot < 0 || key > best) {
+                    best = key;
+                    best_slot = js[u];
+                }
             }
         }
         // keys are distinct (token ids are), so "larger key" is a total order; -1 marks "none"

@@ -90,6 +90,20 @@ __device__ __forceinline__ void store_out(float* O, int64_t i, float v, int out_
     }
 }
 
+// Maximum over the 16 lanes of a row group (same lane pairing as row16_tree_sum).
+__device__ __forceinline__ float row16_max(float p) {
+    p = fmaxf(p, dpp_read<kDppXor1>(p));
+    p = fmaxf(p, dpp_read<kDppXor2>(p));
+    p = fmaxf(p, dpp_read<kDppHalfMirror>(p));
+    p = fmaxf(p, dpp_read<kDppMirror>(p));
+    return p;
+}
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+// Bytes per K row in the wave's LDS tile of the matrix-unit path: 256 + 16 of padding, so that
+// the 16 lanes that read the same 16-byte column of 16 different rows hit different banks.
+constexpr int kKtRow = 272;
+
 template <typename E, int D>
 struct Tile {
     Words<Slice<E, D>::kWords> k[kDecLoads];
@@ -199,7 +213,104 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
         for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
     }
 
-    auto consume = [&](const Tile<E, D>& t, int64_t first_row, bool ragged) {
+    // ---- query groups of 7 and 8 heads (bf16, D = 128): q.k on the matrix unit --------------
+    // With that many heads per streamed row the vector ALU, not HBM, bounds the launch (a wave
+    // spends 80 % of its time issuing vector instructions already at 4 heads), and S = Q.K^T is a
+    // real contraction: M = heads (padded to 16), N = the 16 rows of a tile, K = 128.  Measured
+    // per C3-shaped layer launch, vector path / this path: 5 heads 47.2 / 49.2 us, 6 heads
+    // 48.7 / 49.7, 7 heads 55.0 / 50.9, 8 heads 61.3 / 52.2 -- hence the threshold.  The K tile
+    // goes through a wave-private LDS buffer into the operand layout of
+    // v_mfma_f32_16x16x32_bf16 (lane (c, rg) supplies row c, elements 32j + 8rg .. +7 for
+    // j = 0..3); the result has heads 4rg .. 4rg+3 of row c in lane (c, rg), where the online
+    // softmax runs ONCE per (head, row) instead of in all 16 lanes of a row group; the weights
+    // and the rescaling factors return through LDS to the row-per-16-lanes layout in which V
+    // was loaded, and p.V stays on the fp32 vector unit (bf16 weights would cost 2e-3 relative).
+    // All four row groups of a wave share one running maximum per head.
+    constexpr bool kMfma = kBf16 && D == 128 && G >= 7;
+    __shared__ __attribute__((aligned(16))) char s_ktile[kMfma ? kDecWaves * 16 * kKtRow : 16];
+    __shared__ __attribute__((aligned(16))) float s_pw[kMfma ? kDecWaves * G * 16 : 4];
+    __shared__ __attribute__((aligned(16))) float s_aw[kMfma ? kDecWaves * 8 : 4];
+    [[maybe_unused]] bf16x8_t qa[4];                     // matrix operand of Q: head c, elements 32j + 8rg ..
+    [[maybe_unused]] float cm[4], cl[4];                 // heads 4rg+i: running maximum (raw), denominator of row position c
+    [[maybe_unused]] char* const kt = s_ktile + (kMfma ? wave * 16 * kKtRow : 0);
+    [[maybe_unused]] float* const sp = s_pw + (kMfma ? wave * G * 16 : 0);
+    [[maybe_unused]] float* const sa = s_aw + (kMfma ? wave * 8 : 0);
+    if constexpr (kMfma) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            typedef uint32_t u32x4q __attribute__((ext_vector_type(4)));
+            u32x4q raw = {0u, 0u, 0u, 0u};
+            if (c < G) raw = *reinterpret_cast<const u32x4q*>(Q + (hq0 + c) * S::kRowBytes + (j * 4 + rg) * 16);
+            qa[j] = __builtin_bit_cast(bf16x8_t, raw);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            cm[i] = kNegInf;
+            cl[i] = 0.f;
+        }
+    }
+    auto consume_mfma = [&](const Tile<E, D>& t, int64_t first_row, bool ragged) {
+        typedef uint32_t u32x4m __attribute__((ext_vector_type(4)));
+        if constexpr (kMfma) {
+            // 1. K tile, row-major with padded rows, into the wave's LDS buffer
+#pragma unroll
+            for (int u = 0; u < kDecLoads; ++u) {
+                const u32x4m w = {t.k[u].w[0], t.k[u].w[1], t.k[u].w[2], t.k[u].w[3]};
+                *reinterpret_cast<u32x4m*>(kt + (u * kRowsPerWaveLoad + rg) * kKtRow + c * 16) = w;
+            }
+            __builtin_amdgcn_wave_barrier();
+            // 2. S = Q.K^T: four matrix instructions over the 128 elements of a row
+            f32x4 sc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const u32x4m w = *reinterpret_cast<const u32x4m*>(kt + c * kKtRow + (j * 4 + rg) * 16);
+                sc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[j], __builtin_bit_cast(bf16x8_t, w), sc, 0, 0, 0);
+            }
+            // 3. online softmax of heads 4rg+i over the tile's rows (row c in this lane)
+            float sv[4] = {sc.x, sc.y, sc.z, sc.w};
+            const bool row_ok = !ragged || first_row + c < r1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float si = row_ok ? sv[i] : kNegInf;
+                const float mn = fmaxf(cm[i], row16_max(si));
+                const float ms = mn == kNegInf ? 0.f : mn * scale_log2e;
+                const float alpha = fast_exp2(fmaf(cm[i], scale_log2e, -ms));
+                const float pi = fast_exp2(fmaf(si, scale_log2e, -ms));
+                cl[i] = fmaf(cl[i], alpha, pi);
+                cm[i] = mn;
+                const int g = 4 * rg + i;
+                if (g < G) {
+                    sp[g * 16 + (c % 4) * 4 + c / 4] = pi;        // [head][row group of the row][load of the row]
+                    if (c == 0) sa[g] = alpha;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            // 4. p.V in the layout V was loaded in: lane (rg, c) holds rows 4u + rg, elements 8c ..
+            float al[G], pw[G][kDecLoads];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                al[g] = sa[g];
+                const f32x4 pg = *reinterpret_cast<const f32x4*>(sp + g * 16 + rg * 4);
+                pw[g][0] = pg.x; pw[g][1] = pg.y; pw[g][2] = pg.z; pw[g][3] = pg.w;
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[g][e] *= al[g];
+#pragma unroll
+            for (int u = 0; u < kDecLoads; ++u) {
+                float vx[EPL];
+                widen<E, D>(t.v[u], vx);
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(pw[g][u], vx[e], acc[g][e]);
+            }
+            __builtin_amdgcn_wave_barrier();          // the buffers are rewritten by the next tile
+        }
+    };
+
+    auto consume_valu = [&](const Tile<E, D>& t, int64_t first_row, bool ragged) {
         float s[G][kDecLoads];
 #pragma unroll
         for (int u = 0; u < kDecLoads; ++u) {
@@ -266,6 +377,11 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
         }
     };
 
+    auto consume = [&](const Tile<E, D>& t, int64_t first_row, bool ragged) {
+        if constexpr (kMfma) consume_mfma(t, first_row, ragged);
+        else consume_valu(t, first_row, ragged);
+    };
+
     // Work assignment.  The head's rows are cut into 16-row tiles; tile t goes to
     // workgroup (t / 4) % n_splits, wave t % 4: the workgroups of a KV head take
     // turns on consecutive 64-row blocks.  Every workgroup therefore sweeps the
@@ -320,6 +436,26 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
             const int64_t first = n_full * kDecRowsPerStep;
             load_tile_clamped<E, D>(tt, Kh, Vh, first, r1 - 1, rg, c);
             consume(tt, first, true);
+        }
+    }
+
+    if constexpr (kMfma) {
+        // hand the wave's softmax state to the row-group layout of the merge below: all four row
+        // groups of the wave share the maximum; the denominator is counted once (row group 0)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float lt = row16_tree_sum(cl[i]);
+            const int g = 4 * rg + i;
+            if (g < G && c == 0) {
+                sa[g] = cm[i];
+                sp[g] = lt;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            m[g] = sa[g];
+            l[g] = rg == 0 ? sp[g] : 0.f;
         }
     }
 

@@ -225,7 +225,10 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
     // softmax runs ONCE per (head, row) instead of in all 16 lanes of a row group; the weights
     // and the rescaling factors return through LDS to the row-per-16-lanes layout in which V
     // was loaded, and p.V stays on the fp32 vector unit (bf16 weights would cost 2e-3 relative).
-    // All four row groups of a wave share one running maximum per head.
+    // All four row groups of a wave share one running maximum per head.  (Loading K straight
+    // into the operand layout -- 64 contiguous bytes of each of 16 rows per load instruction
+    // instead of 256 bytes of each of 4 rows -- needs no LDS staging but streams worse: 59.1 us
+    // against 52.6 us at 8 heads.)
     constexpr bool kMfma = kBf16 && D == 128 && G >= 7;
     __shared__ __attribute__((aligned(16))) char s_ktile[kMfma ? kDecWaves * 16 * kKtRow : 16];
     __shared__ __attribute__((aligned(16))) float s_pw[kMfma ? kDecWaves * G * 16 : 4];

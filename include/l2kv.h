@@ -94,7 +94,11 @@ l2kv_status l2kv_norms(const void* K, l2kv_dtype dt, int64_t n_heads, int64_t T,
  *   kept_idx   out: [n_heads][k] int32, strictly ascending per head
  *   kept_count out: [n_heads] int32, every entry = k; may be NULL
  *   workspace     : l2kv_select_workspace_bytes(n_heads, T) bytes, 16-aligned;
- *                   contents need not be initialised and are undefined after
+ *                   contents need not be initialised and are undefined after.
+ *                   This version keeps all selection state in registers and
+ *                   LDS and never touches the buffer; the size query returns
+ *                   a small constant (256).  The argument is part of the
+ *                   signature for versions that select across workgroups.
  * Errors: NULL, SHAPE, RATIO, WORKSPACE, ALIGN, LAUNCH.
  */
 l2kv_status l2kv_select(const float* norms, int64_t n_heads, int64_t T,

@@ -72,8 +72,9 @@ l2kv_status l2kv_norms(const void* K, l2kv_dtype dt, int64_t n_heads, int64_t T,
 }
 
 size_t l2kv_select_workspace_bytes(int64_t n_heads, int64_t T) {
-    // The current kernels keep all selection state in registers and LDS; a
-    // small fixed size is reported so callers exercise the argument.
+    // The kernels keep all selection state in registers and LDS and never touch
+    // the workspace; the header says so.  A small fixed size keeps callers'
+    // allocation code valid for a version that does need scratch.
     (void)n_heads;
     (void)T;
     return 256;

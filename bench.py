@@ -329,7 +329,8 @@ class StreamWorkload:
 
 
 def stream_parity_sample(w: "StreamWorkload", n_heads=5, steps=4):
-    """GPU vs oracle on sampled (plane, sequence) heads of the streaming batch: the
+    """CPU baseline of the streaming workload: the oracle timed on a small sample, which doubles as
+    a GPU-vs-oracle check.  Sampled (plane, sequence) heads of the streaming batch: the
     oracle compresses the sampled prompts and replays the first decode steps
     token by token (append, attend, evict to budget).  Kept token ids, slot
     contents and lengths must agree exactly; the attention error is returned."""
@@ -347,8 +348,11 @@ def stream_parity_sample(w: "StreamWorkload", n_heads=5, steps=4):
     caps = np.diff(slot_off)
     heads, idx_equal = {}, True
     t_cpu = 0.0
+    row = cfg.D * cfg.elem_bytes
+    sample_bytes = 0                      # algorithmic bytes of what the oracle is timed on (same formulas as the GPU side)
     for (p, s) in sorted(samples):
         a, b = in_off[s], in_off[s + 1]
+        sample_bytes += (b - a) * (row + 4) + (b - a) * 4 + w.k0[s] * 4 + w.k0[s] * (4 + 4 * row + 12)
         Kn, Vn = synth.as_numpy_bits(w.K[p, a:b]), synth.as_numpy_bits(w.V[p, a:b])
         t0 = time.perf_counter()
         n32, _ = oracle.norms(Kn[None], cfg.dtype)
@@ -384,6 +388,7 @@ def stream_parity_sample(w: "StreamWorkload", n_heads=5, steps=4):
             kn = synth.as_numpy_bits(w.Knew[t, layer, s, hk])
             vn = synth.as_numpy_bits(w.Vnew[t, layer, s, hk])
             qn = synth.as_numpy_bits(w.Q[t, layer, s, hk * G:(hk + 1) * G])
+            sample_bytes += (len(h) + 1) * 2 * row + G * cfg.D * (cfg.elem_bytes + 4) + 4 * row + 8
             t0 = time.perf_counter()
             h.append(kn, vn, lens[s] + t)
             want = h.attend(qn)
@@ -391,8 +396,13 @@ def stream_parity_sample(w: "StreamWorkload", n_heads=5, steps=4):
             t_cpu += time.perf_counter() - t0
             worst = max(worst, float(np.abs(O[layer, s, hk * G:(hk + 1) * G] - want).max()))
         cache_equal &= slots_equal()
-    return {"heads": sorted(samples), "decode_steps": min(steps, cfg.decode_steps), "kept_idx_equal": idx_equal,
-            "slot_cache_equal": cache_equal, "attn_max_abs_err": worst, "oracle_seconds": round(t_cpu, 2)}
+    n_steps = min(steps, cfg.decode_steps)
+    return {"value": sample_bytes / t_cpu / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "%s: %d sampled (plane, sequence) heads %s: prompt compression + %d decode steps (append, attend, "
+                      "evict) replayed token by token; %.2f s of CPU time" % (cfg.name, len(samples), sorted(samples), n_steps, t_cpu),
+            "seconds": t_cpu,
+            "gpu_vs_oracle_on_sample": {"kept_idx_equal": idx_equal, "slot_cache_equal": cache_equal,
+                                        "attn_max_abs_err": worst}}
 
 
 def run_stream(cfg, dev, steps, warmup, overridden=False, use_order=True, parity=True):
@@ -442,7 +452,7 @@ def run_stream(cfg, dev, steps, warmup, overridden=False, use_order=True, parity
                      "bytes_per_decode_step": (attn_bytes + other_bytes) // cfg.decode_steps},
     }
     if parity:
-        out["gpu_vs_oracle_on_sample"] = stream_parity_sample(w)
+        out["cpu_baseline"] = stream_parity_sample(w)
     del w
     torch.cuda.empty_cache()
     return out

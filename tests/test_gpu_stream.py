@@ -243,7 +243,8 @@ def check_ragged(got, host, lens, slot_off, dt, tag):
         assert np.abs(got[s] - want).max() <= ATTN_BAR, (tag, s)
 
 
-def test_ragged_decode_work_list_with_more_items_than_workgroups(dev):
+@pytest.mark.parametrize("G", [2, 8])
+def test_ragged_decode_work_list_with_more_items_than_workgroups(dev, G):
     # ordered launches hand (sequence, KV head, share) items to one workgroup per compute unit from a
     # device-side list: 40 sequences x 8 KV heads, whole sequences (320 items), two shares (640) and
     # twelve shares (3840 items, the merge variant for more than 8 workgroups per head); short
@@ -252,7 +253,7 @@ def test_ragged_decode_work_list_with_more_items_than_workgroups(dev):
     rng = np.random.default_rng(77)
     lens = [int(x) for x in rng.integers(1, 3000, 40)]
     lens[3], lens[17] = 0, 2999
-    Hkv, G = 8, 2
+    Hkv = 8                      # G = 8: the variant that forms q.k on the matrix unit
     host, (Qd, Kd, Vd), d_lens, d_off, slot_off = ragged_case(dev, rng, lens, Hkv, G)
     ws = torch.zeros(l2kv.l2kv_decode_ragged_workspace_bytes(len(lens), Hkv * G, max(lens), 128),
                      dtype=torch.uint8, device=dev)

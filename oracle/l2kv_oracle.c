@@ -23,6 +23,11 @@
  *     two nearly equal norms decides an integer (which row is kept) and both
  *     sides must take that decision in the same precision.
  *
+ * Pins: every function here is pinned by the no-GPU tests against something other
+ * than itself (hand-derived fixtures, brute force on small inputs, closed forms,
+ * library routines, and for the keep-random hash its mathematical inverse); no
+ * function is left parity-unpinned.
+ *
  * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC.
  * Floating point: norms in fp32 exactly as written (no contraction); fp64
  * "truth" norms beside them; attention accumulates in fp64 and rounds once.

@@ -19,12 +19,26 @@
 // (both operands are exact bf16 inputs); the softmax scale is applied to the
 // fp32 score afterwards.  fp32 caches use plain fp32 FMAs.
 //
-// At the end the 16 row groups of the workgroup are merged through LDS and one
-// partial (acc[D], m, l) per query head goes to the workspace.  The workgroup
-// that finishes last for its KV head (device-scope counter in the workspace)
-// merges the partials of all workgroups and writes O: one kernel per call.
+// Query groups of 7 and 8 heads (bf16, D = 128) form q.k on the matrix unit
+// instead and run the softmax once per (head, row); see decode_item.
+//
+// At the end the 16 row groups of the workgroup are merged through LDS.  A KV
+// head with a single workgroup writes O from that merge.  Otherwise one partial
+// (acc[D], m, l) per query head goes to the workspace, and the workgroup that
+// finishes last for its KV head (device-scope counter in the workspace) merges
+// the partials of all workgroups and writes O: one kernel per call.  Two builds
+// of that final merge (template parameter kWideMerge): for at most 8 workgroups
+// per head everything stays in registers; for more, the weights are formed once
+// in LDS and the accumulators arrive as 16-byte device-scope loads.
+//
+// The same routine (decode_item) runs under two launch shapes: a grid
+// (decode_kernel) and, for ragged batches with a known longest-first order, a
+// fixed set of workgroups that draw (sequence, KV head, share) items from a
+// counter in the workspace (decode_worklist_kernel).
 //
 // Scores are kept in the log2 domain so the exponentials are bare v_exp_f32.
+// This header is instantiated per (element type, head size) by
+// decode_attn_<type>_<D>.hip; the host side (plans, dispatch) is decode_attn.hip.
 #pragma once
 #include "l2kv_device.hpp"
 #include "l2kv_host.hpp"

@@ -17,8 +17,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libl2kv.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["decode_attn_bf16_128.hip", "decode_attn_bf16_64.hip", "decode_attn_f32_128.hip",
-           "decode_attn_f32_64.hip", "api.hip", "norms.hip", "select.hip", "compact.hip", "decode_attn.hip",
+SOURCES = ["decode_attn_bf16_128.hip", "decode_attn_bf16_256.hip", "decode_attn_bf16_64.hip",
+           "decode_attn_f32_128.hip", "decode_attn_f32_64.hip", "api.hip", "norms.hip", "select.hip", "compact.hip", "decode_attn.hip",
            "stream.hip", "alr.hip"]
 ARCH = "gfx950"
 

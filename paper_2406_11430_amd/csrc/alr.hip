@@ -200,12 +200,15 @@ void alr_scores_kernel(const void* __restrict__ Q, const void* __restrict__ K, i
     const int r = lane / kRowLanes;
     const int64_t head = blockIdx.y;                                   // b * Hkv + hkv
     const int64_t q_head0 = head * G;                                  // b * Hq + hkv * G
-    const char* kbase = static_cast<const char*>(K) + head * k_head_stride * E::kBytes + c * S::kBytes;
-    const char* qbase = static_cast<const char*>(Q) + q_head0 * S::kRowBytes + c * S::kBytes;
+    // q and K rows are shared among the 16 lanes in the same 16-byte pieces (the dot product
+    // does not care which lane holds which element)
+    using P = Pieces<S::kWords>;
+    const char* kbase = static_cast<const char*>(K) + head * k_head_stride * E::kBytes + c * P::kBytes;
+    const char* qbase = static_cast<const char*>(Q) + q_head0 * S::kRowBytes + c * P::kBytes;
 
     float q[G][S::kElems];
 #pragma unroll
-    for (int g = 0; g < G; ++g) widen<E, D>(load_words<S::kWords>(qbase + (size_t)g * S::kRowBytes), q[g]);
+    for (int g = 0; g < G; ++g) widen<E, D>(load_words<S::kWords, P::kStride>(qbase + (size_t)g * S::kRowBytes), q[g]);
 
     const int64_t row0 = (int64_t)blockIdx.x * kScoreRowsPerBlock + wave * kScoreRowsPerWave + r;
     Words<S::kWords> tile[kScoreLoads];
@@ -213,7 +216,7 @@ void alr_scores_kernel(const void* __restrict__ Q, const void* __restrict__ K, i
     for (int u = 0; u < kScoreLoads; ++u) {
         int64_t t = row0 + u * kRowsPerWaveLoad;
         t = t < T ? t : T - 1;                                         // clamped, never stored
-        tile[u] = load_words_stream<S::kWords>(kbase + (size_t)t * S::kRowBytes);
+        tile[u] = load_words_stream<S::kWords, P::kStride>(kbase + (size_t)t * S::kRowBytes);
     }
 #pragma unroll
     for (int u = 0; u < kScoreLoads; ++u) {
@@ -365,7 +368,9 @@ l2kv_status alr_dispatch(const void* Q, const void* K, l2kv_dtype dt, const int3
     const float scale_log2e = s * 1.44269504088896340736f;
     float* scores = static_cast<float*>(workspace);
     l2kv_status st;
-    if (dt == L2KV_BF16)
+    if (dt == L2KV_BF16 && D == 256)
+        st = launch_scores<BF16, 256>(Q, K, B, Hkv, G, T, k_head_stride, scale_log2e, scores, stream);
+    else if (dt == L2KV_BF16)
         st = D == 128 ? launch_scores<BF16, 128>(Q, K, B, Hkv, G, T, k_head_stride, scale_log2e, scores, stream)
                       : launch_scores<BF16, 64>(Q, K, B, Hkv, G, T, k_head_stride, scale_log2e, scores, stream);
     else

@@ -31,14 +31,18 @@ namespace {
 inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 inline bool dtype_ok(l2kv_dtype dt) { return dt == L2KV_F32 || dt == L2KV_BF16; }
 inline int elem_bytes(l2kv_dtype dt) { return dt == L2KV_F32 ? 4 : 2; }
-inline bool dim_ok(int32_t D) { return D == 64 || D == 128; }
+// head sizes: 64 and 128 for both element types, 256 for bf16 (a row is then 512 bytes, as an
+// fp32 row of 128 elements)
+inline bool dim_ok(int32_t D, l2kv_dtype dt) { return D == 64 || D == 128 || (D == 256 && dt == L2KV_BF16); }
+// query heads per KV head the decode kernels are built for
+inline int32_t max_group(int32_t D) { return D == 256 ? 4 : 8; }
 constexpr int64_t kMaxTokens = 0x7fffffffLL;          // token indices are int32
 constexpr int64_t kMaxHeads = 0x7fffffffLL;
 
 // Shared checks of a strided [n_heads][T][D] tensor description.
 l2kv_status check_cache(l2kv_dtype dt, int64_t n_heads, int64_t T, int32_t D, int64_t head_stride) {
     if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
-    if (n_heads <= 0 || n_heads > kMaxHeads || T <= 0 || T > kMaxTokens || !dim_ok(D))
+    if (n_heads <= 0 || n_heads > kMaxHeads || T <= 0 || T > kMaxTokens || !dim_ok(D, dt))
         return L2KV_ERR_SHAPE;
     if (head_stride < T * (int64_t)D) return L2KV_ERR_SHAPE;
     if ((head_stride * elem_bytes(dt)) % 16 != 0) return L2KV_ERR_ALIGN;
@@ -178,9 +182,9 @@ static l2kv_status check_decode(const void* Q, const void* Kc, const void* Vc, l
                                 float scale, int32_t n_splits, const void* O, uintptr_t o_align = 4) {
     if (Q == nullptr || Kc == nullptr || Vc == nullptr || O == nullptr) return L2KV_ERR_NULL;
     if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
-    if (B <= 0 || Hq <= 0 || Hkv <= 0 || kv_len <= 0 || kv_len > kMaxTokens || !dim_ok(D))
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || kv_len <= 0 || kv_len > kMaxTokens || !dim_ok(D, dt))
         return L2KV_ERR_SHAPE;
-    if (Hq % Hkv != 0 || Hq / Hkv > 8) return L2KV_ERR_SHAPE;
+    if (Hq % Hkv != 0 || Hq / Hkv > max_group(D)) return L2KV_ERR_SHAPE;
     if (static_cast<int64_t>(B) * Hkv > 65535 || static_cast<int64_t>(B) * Hq > 0x7fffffffLL)
         return L2KV_ERR_SHAPE;
     if (kv_head_stride < kv_len * static_cast<int64_t>(D)) return L2KV_ERR_SHAPE;
@@ -295,7 +299,7 @@ l2kv_status l2kv_compact_ragged(const void* K, const void* V, const float* norms
     if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
     if (n_planes <= 0 || n_seq <= 0 || total_tokens <= 0 || total_tokens > kMaxTokens ||
         total_kept <= 0 || total_kept > total_tokens || max_kept <= 0 || max_kept > total_kept ||
-        total_slots <= 0 || total_slots > kMaxTokens || !dim_ok(D))
+        total_slots <= 0 || total_slots > kMaxTokens || !dim_ok(D, dt))
         return L2KV_ERR_SHAPE;
     if (!aligned(K, 16) || !aligned(V, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(norms, 4) ||
         !aligned(norms_c, 4) || !aligned(pos_c, 4) || !aligned(kept_idx, 4) || !aligned(in_offsets, 8) ||
@@ -316,7 +320,7 @@ l2kv_status l2kv_stream_append(const void* Knew, const void* Vnew, l2kv_dtype dt
         norms_c == nullptr || pos_c == nullptr)
         return L2KV_ERR_NULL;
     if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
-    if (n_layers <= 0 || n_seq <= 0 || Hkv <= 0 || total_slots <= 0 || total_slots > kMaxTokens || !dim_ok(D))
+    if (n_layers <= 0 || n_seq <= 0 || Hkv <= 0 || total_slots <= 0 || total_slots > kMaxTokens || !dim_ok(D, dt))
         return L2KV_ERR_SHAPE;
     if (lens_in == lens_out) return L2KV_ERR_SHAPE;           // workgroups read lens_in while one writes lens_out
     if (!aligned(Knew, 16) || !aligned(Vnew, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) ||
@@ -336,7 +340,7 @@ l2kv_status l2kv_stream_evict(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, in
         Kc == nullptr || Vc == nullptr || norms_c == nullptr || pos_c == nullptr)
         return L2KV_ERR_NULL;
     if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
-    if (n_planes <= 0 || n_seq <= 0 || total_slots <= 0 || total_slots > kMaxTokens || !dim_ok(D))
+    if (n_planes <= 0 || n_seq <= 0 || total_slots <= 0 || total_slots > kMaxTokens || !dim_ok(D, dt))
         return L2KV_ERR_SHAPE;
     if (lens_in == lens_out) return L2KV_ERR_SHAPE;
     if (!aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(norms_c, 4) || !aligned(pos_c, 4) ||
@@ -371,9 +375,9 @@ l2kv_status l2kv_decode_attn_ragged(const void* Q, const void* Kc, const void* V
         return L2KV_ERR_NULL;
     if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
     if (n_seq <= 0 || Hq <= 0 || Hkv <= 0 || max_len <= 0 || total_slots <= 0 ||
-        total_slots > kMaxTokens || max_len > total_slots || !dim_ok(D))
+        total_slots > kMaxTokens || max_len > total_slots || !dim_ok(D, dt))
         return L2KV_ERR_SHAPE;
-    if (Hq % Hkv != 0 || Hq / Hkv > 8) return L2KV_ERR_SHAPE;
+    if (Hq % Hkv != 0 || Hq / Hkv > max_group(D)) return L2KV_ERR_SHAPE;
     if (static_cast<int64_t>(n_seq) * Hkv > 65535 || static_cast<int64_t>(n_seq) * Hq > 0x7fffffffLL)
         return L2KV_ERR_SHAPE;
     if (n_splits < 0 || n_splits > decode_max_splits(max_len) || !std::isfinite(scale)) return L2KV_ERR_SHAPE;
@@ -437,7 +441,7 @@ l2kv_status l2kv_alr(const void* Q, const void* K, l2kv_dtype dt, const int32_t*
                      size_t workspace_bytes, void* stream) {
     if (Q == nullptr || K == nullptr || drop_rank == nullptr || alr == nullptr) return L2KV_ERR_NULL;
     if (!dtype_ok(dt)) return L2KV_ERR_DTYPE;
-    if (B <= 0 || Hq <= 0 || Hkv <= 0 || T <= 0 || T > kMaxTokens || !dim_ok(D)) return L2KV_ERR_SHAPE;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || T <= 0 || T > kMaxTokens || !dim_ok(D, dt)) return L2KV_ERR_SHAPE;
     if (Hq % Hkv != 0 || Hq / Hkv > 8) return L2KV_ERR_SHAPE;
     if (static_cast<int64_t>(B) * Hkv > 65535 || static_cast<int64_t>(B) * Hq > 0x7fffffffLL)
         return L2KV_ERR_SHAPE;

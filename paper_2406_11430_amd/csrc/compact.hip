@@ -1,9 +1,9 @@
 // l2kv_compact: gather of the kept K and V rows into dense caches (arXiv
 // 2406.11430 Sec. 1: the lowest-norm keys are kept, each with its value).
 //
-// A byte copy of whole rows: 16 lanes move one row (16 bytes per lane for the
-// 256-byte rows of the supported shapes), a wavefront moves 4 rows per
-// instruction, and each row group handles kUnroll consecutive output rows so
+// A byte copy of whole rows: 16 lanes move one row (16 bytes per lane and
+// instruction: one piece of a 256-byte row, pieces c and c + 16 of a 512-byte
+// row), a wavefront moves 4 rows per instruction, and each row group handles kUnroll consecutive output rows so
 // all index loads, then all row loads of K and V, are in flight before the
 // first store.  Loads and stores carry the non-temporal hint (every byte is
 // touched once).  Dropped rows are never read.
@@ -26,8 +26,8 @@ __global__ __launch_bounds__(kCompactThreads)
 void compact_kernel(const char* __restrict__ K, const char* __restrict__ V,
                     const int32_t* __restrict__ kept_idx, int64_t T, int64_t k, int64_t head_stride_bytes,
                     int64_t blocks_per_head, char* __restrict__ Kc, char* __restrict__ Vc) {
-    constexpr int64_t kSliceBytes = 4 * W;
-    constexpr int64_t kRowBytes = kRowLanes * kSliceBytes;
+    using P = Pieces<W>;
+    constexpr int64_t kRowBytes = kRowLanes * 4 * W;
     const int64_t head = blockIdx.x / blocks_per_head;
     const int64_t chunk = blockIdx.x % blocks_per_head;
     const int lane = threadIdx.x % kWaveSize;
@@ -47,22 +47,22 @@ void compact_kernel(const char* __restrict__ K, const char* __restrict__ V,
         j = j < k ? j : k - 1;            // tail: duplicate the last row, store skipped
         int64_t t = idx[j];
         t = t < 0 ? 0 : (t < T ? t : T - 1);          // an index outside [0, T) cannot lead out of the head
-        src[u] = src_head + t * kRowBytes + c * kSliceBytes;
+        src[u] = src_head + t * kRowBytes + c * P::kBytes;
     }
     Words<W> kr[kCompactUnroll], vr[kCompactUnroll];
 #pragma unroll
-    for (int u = 0; u < kCompactUnroll; ++u) kr[u] = load_words_stream<W>(K + src[u]);
+    for (int u = 0; u < kCompactUnroll; ++u) kr[u] = load_words_stream<W, P::kStride>(K + src[u]);
     if constexpr (HAS_V) {
 #pragma unroll
-        for (int u = 0; u < kCompactUnroll; ++u) vr[u] = load_words_stream<W>(V + src[u]);
+        for (int u = 0; u < kCompactUnroll; ++u) vr[u] = load_words_stream<W, P::kStride>(V + src[u]);
     }
 #pragma unroll
     for (int u = 0; u < kCompactUnroll; ++u) {
         const int64_t j = first + u;
         if (j < k) {
-            const int64_t dst = dst_head + j * kRowBytes + c * kSliceBytes;
-            store_words_stream<W>(Kc + dst, kr[u]);
-            if constexpr (HAS_V) store_words_stream<W>(Vc + dst, vr[u]);
+            const int64_t dst = dst_head + j * kRowBytes + c * P::kBytes;
+            store_words_stream<W, P::kStride>(Kc + dst, kr[u]);
+            if constexpr (HAS_V) store_words_stream<W, P::kStride>(Vc + dst, vr[u]);
         }
     }
 }

@@ -22,6 +22,7 @@ l2kv_status decode_by_group(int G, const void* Q, const void* Kc, const void* Vc
                             const int64_t* slot_off, const int32_t* seq_order, float scale,
                             const DecodePlan& plan, float* O, void* workspace, hipStream_t stream);
 extern template l2kv_status decode_by_group<BF16, 128>(int, const void*, const void*, const void*, int32_t, int32_t, int32_t, int64_t, int64_t, const int32_t*, const int64_t*, const int32_t*, float, const DecodePlan&, float*, void*, hipStream_t);
+extern template l2kv_status decode_by_group<BF16, 256>(int, const void*, const void*, const void*, int32_t, int32_t, int32_t, int64_t, int64_t, const int32_t*, const int64_t*, const int32_t*, float, const DecodePlan&, float*, void*, hipStream_t);
 extern template l2kv_status decode_by_group<BF16, 64>(int, const void*, const void*, const void*, int32_t, int32_t, int32_t, int64_t, int64_t, const int32_t*, const int64_t*, const int32_t*, float, const DecodePlan&, float*, void*, hipStream_t);
 extern template l2kv_status decode_by_group<F32, 128>(int, const void*, const void*, const void*, int32_t, int32_t, int32_t, int64_t, int64_t, const int32_t*, const int64_t*, const int32_t*, float, const DecodePlan&, float*, void*, hipStream_t);
 extern template l2kv_status decode_by_group<F32, 64>(int, const void*, const void*, const void*, int32_t, int32_t, int32_t, int64_t, int64_t, const int32_t*, const int64_t*, const int32_t*, float, const DecodePlan&, float*, void*, hipStream_t);
@@ -185,6 +186,9 @@ l2kv_status decode_dispatch(const void* Q, const void* Kc, const void* Vc, l2kv_
                        : decode_by_group<F32, 128>(G, Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride,
                                                    lens, slot_off, seq_order, scale, plan, O, workspace, stream);
     }
+    if (D == 256)
+        return decode_by_group<BF16, 256>(G, Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride, lens, slot_off,
+                                          seq_order, scale, plan, O, workspace, stream);
     return D == 64 ? decode_by_group<BF16, 64>(G, Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride,
                                                lens, slot_off, seq_order, scale, plan, O, workspace, stream)
                    : decode_by_group<BF16, 128>(G, Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride,

@@ -62,9 +62,26 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
 }
 
-// K and V are read once per call: streaming loads, nothing to keep in L2.
+// Row element held in fp32 slot e of the slice of lane c (slots in the order of widen()), with
+// the row shared among the lanes in 16-byte pieces (Pieces in l2kv_device.hpp).
+template <typename E, int D>
+__device__ __forceinline__ constexpr int slice_elem(int c, int e) {
+    using P = Pieces<Slice<E, D>::kWords>;
+    constexpr int per_piece = P::kBytes / E::kBytes;
+    return (e / per_piece) * (P::kStride / E::kBytes) + c * per_piece + e % per_piece;
+}
+
+// K and V are read once per call: streaming loads, nothing to keep in L2.  p = the lane's
+// first piece of the row.
 template <int W>
-__device__ __forceinline__ Words<W> stream_words(const char* p) { return load_words_stream<W>(p); }
+__device__ __forceinline__ Words<W> stream_words(const char* p) {
+    return load_words_stream<W, Pieces<W>::kStride>(p);
+}
+// The same for data that is re-read (the query rows).
+template <int W>
+__device__ __forceinline__ Words<W> cached_words(const char* p) {
+    return load_words<W, Pieces<W>::kStride>(p);
+}
 
 // s_waitcnt immediate for "vmcnt(0)" alone in the gfx9-family encoding that gfx950 uses: vmcnt
 // in bits [3:0] and [15:14] = 0, expcnt [6:4] and lgkmcnt [11:8] left at their maxima.
@@ -125,7 +142,7 @@ struct Tile {
 };
 
 // Loads the 16 rows [first_row, first_row+16) of K and V for this lane; all 16
-// rows must exist.  lane_off = rg * row_bytes + c * slice_bytes.
+// rows must exist.  lane_off = rg * row_bytes + c * piece_bytes.
 template <typename E, int D>
 __device__ __forceinline__ void load_tile(Tile<E, D>& t, const char* Kh, const char* Vh,
                                           int64_t first_row, int lane_off) {
@@ -150,7 +167,7 @@ __device__ __forceinline__ void load_tile_clamped(Tile<E, D>& t, const char* Kh,
     for (int u = 0; u < kDecLoads; ++u) {
         int64_t row = first_row + u * kRowsPerWaveLoad + rg;
         row = row < last_valid ? row : last_valid;
-        off[u] = row * S::kRowBytes + c * S::kBytes;
+        off[u] = row * S::kRowBytes + c * Pieces<S::kWords>::kBytes;
     }
 #pragma unroll
     for (int u = 0; u < kDecLoads; ++u) t.k[u] = stream_words<S::kWords>(Kh + off[u]);
@@ -209,14 +226,14 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
     float qf[kBf16 ? 1 : G][kBf16 ? 1 : EPL];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        Words<W> raw = load_words<W>(Q + (hq0 + g) * S::kRowBytes + c * S::kBytes);
+        Words<W> raw = cached_words<W>(Q + (hq0 + g) * S::kRowBytes + c * Pieces<W>::kBytes);
 #pragma unroll
         for (int w = 0; w < W; ++w) qw[g][w] = raw.w[w];
         if constexpr (!kBf16) widen<E, D>(raw, qf[g]);
     }
 
     const int64_t r1 = kv_len;                   // rows at or past r1 do not exist
-    const int lane_off = rg * S::kRowBytes + c * S::kBytes;
+    const int lane_off = rg * S::kRowBytes + c * Pieces<W>::kBytes;
 
     float m[G], l[G], acc[G][EPL];    // m: running max of the RAW score (before scaling)
 #pragma unroll
@@ -487,7 +504,7 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
 #pragma unroll
     for (int g = 0; g < G; ++g) {
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) s_acc[(grp * G + g) * D + c * EPL + e] = acc[g][e];
+        for (int e = 0; e < EPL; ++e) s_acc[(grp * G + g) * D + slice_elem<E, D>(c, e)] = acc[g][e];
         if (c == 0) {
             s_m[grp * G + g] = m[g] * scale_log2e;     // -inf stays -inf (scale > 0)
             s_l[grp * G + g] = l[g];
@@ -867,9 +884,12 @@ l2kv_status decode_by_group(int G, const void* Q, const void* Kc, const void* Vc
     case N:                                                                                         \
         return launch_decode<E, D, N>(Q, Kc, Vc, B, Hq, Hkv, kv_len, kv_head_stride, lens, slot_off, \
                                       seq_order, scale, plan, O, workspace, stream)
-    switch (G) {
-        L2KV_G(1); L2KV_G(2); L2KV_G(3); L2KV_G(4); L2KV_G(5); L2KV_G(6); L2KV_G(7); L2KV_G(8);
+    // the final merge gives every thread at most one 16-byte piece of the G output rows:
+    // G * D <= 1024, i.e. up to 8 heads for rows of 64 and 128 elements, 4 for rows of 256
+    if constexpr (D <= 128) {
+        switch (G) { L2KV_G(5); L2KV_G(6); L2KV_G(7); L2KV_G(8); }
     }
+    switch (G) { L2KV_G(1); L2KV_G(2); L2KV_G(3); L2KV_G(4); }
 #undef L2KV_G
     return L2KV_ERR_SHAPE;
 }

@@ -50,7 +50,22 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __builtin_bit_cast
 // A lane's slice of a row as W 32-bit words (W = 2, 4 or 8).
 template <int W> struct Words { uint32_t w[W]; };
 
-template <int W>
+// How the 16 lanes of a row group share a row in the kernels whose result does not depend on
+// which lane holds which element (row copies, dot products with both operands laid out alike):
+// lane c takes the 16-byte pieces c, c + 16, ... of the row -- one piece of a 256-byte row, two
+// of a 512-byte row, one 8-byte piece of a 128-byte row -- so that every load or store
+// instruction of a row group covers contiguous bytes.  (Consecutive 32 bytes per lane make each
+// instruction touch every second 16 bytes of a 512-byte row; measured on decode attention over
+// such rows: 57 us against 43 us per launch.)  The loads and stores below take the byte distance
+// between a lane's 16-byte pieces as kPieceStride: 16 = consecutive, Pieces<W>::kStride = shared
+// as described, with p = row + c * Pieces<W>::kBytes.
+template <int W> struct Pieces {
+    static constexpr int kCount = W >= 4 ? W / 4 : 1;
+    static constexpr int kBytes = 4 * W / kCount;                // bytes per piece
+    static constexpr int kStride = kRowLanes * kBytes;           // bytes between a lane's pieces
+};
+
+template <int W, int kPieceStride = 16>
 __device__ __forceinline__ Words<W> load_words(const void* p) {
     Words<W> r;
     if constexpr (W == 2) {
@@ -60,7 +75,7 @@ __device__ __forceinline__ Words<W> load_words(const void* p) {
         static_assert(W % 4 == 0, "slice must be 8 bytes or a multiple of 16");
 #pragma unroll
         for (int i = 0; i < W / 4; ++i) {
-            uint4 v = reinterpret_cast<const uint4*>(p)[i];
+            uint4 v = *reinterpret_cast<const uint4*>(static_cast<const char*>(p) + i * kPieceStride);
             r.w[4 * i + 0] = v.x; r.w[4 * i + 1] = v.y;
             r.w[4 * i + 2] = v.z; r.w[4 * i + 3] = v.w;
         }
@@ -70,7 +85,7 @@ __device__ __forceinline__ Words<W> load_words(const void* p) {
 
 // Streaming variants: data that is read or written exactly once per call and
 // should not displace anything in the caches (non-temporal hint).
-template <int W>
+template <int W, int kPieceStride = 16>
 __device__ __forceinline__ Words<W> load_words_stream(const void* p) {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -81,14 +96,15 @@ __device__ __forceinline__ Words<W> load_words_stream(const void* p) {
     } else {
 #pragma unroll
         for (int i = 0; i < W / 4; ++i) {
-            u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p) + i);
+            u32x4 v = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4*>(static_cast<const char*>(p) + i * kPieceStride));
             r.w[4 * i + 0] = v.x; r.w[4 * i + 1] = v.y; r.w[4 * i + 2] = v.z; r.w[4 * i + 3] = v.w;
         }
     }
     return r;
 }
 
-template <int W>
+template <int W, int kPieceStride = 16>
 __device__ __forceinline__ void store_words_stream(void* p, const Words<W>& r) {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -99,19 +115,19 @@ __device__ __forceinline__ void store_words_stream(void* p, const Words<W>& r) {
 #pragma unroll
         for (int i = 0; i < W / 4; ++i) {
             u32x4 v = {r.w[4 * i + 0], r.w[4 * i + 1], r.w[4 * i + 2], r.w[4 * i + 3]};
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p) + i);
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(static_cast<char*>(p) + i * kPieceStride));
         }
     }
 }
 
-template <int W>
+template <int W, int kPieceStride = 16>
 __device__ __forceinline__ void store_words(void* p, const Words<W>& r) {
     if constexpr (W == 2) {
         *reinterpret_cast<uint2*>(p) = make_uint2(r.w[0], r.w[1]);
     } else {
 #pragma unroll
         for (int i = 0; i < W / 4; ++i)
-            reinterpret_cast<uint4*>(p)[i] =
+            *reinterpret_cast<uint4*>(static_cast<char*>(p) + i * kPieceStride) =
                 make_uint4(r.w[4 * i + 0], r.w[4 * i + 1], r.w[4 * i + 2], r.w[4 * i + 3]);
     }
 }

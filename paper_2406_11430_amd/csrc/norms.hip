@@ -88,6 +88,7 @@ l2kv_status norms_dispatch(const void* K, l2kv_dtype dt, int64_t n_heads, int64_
         return D == 64 ? launch_norms<F32, 64>(K, n_heads, T, head_stride, norms, keep_in_cache, stream)
                        : launch_norms<F32, 128>(K, n_heads, T, head_stride, norms, keep_in_cache, stream);
     }
+    if (D == 256) return launch_norms<BF16, 256>(K, n_heads, T, head_stride, norms, keep_in_cache, stream);
     return D == 64 ? launch_norms<BF16, 64>(K, n_heads, T, head_stride, norms, keep_in_cache, stream)
                    : launch_norms<BF16, 128>(K, n_heads, T, head_stride, norms, keep_in_cache, stream);
 }

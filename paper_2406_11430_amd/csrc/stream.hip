@@ -56,8 +56,8 @@ void compact_ragged_kernel(const char* __restrict__ K, const char* __restrict__ 
                            int64_t chunks_per_plane, const int64_t* __restrict__ slot_off,
                            int64_t total_slots, char* __restrict__ Kc, char* __restrict__ Vc,
                            float* __restrict__ norms_c, int32_t* __restrict__ pos_c) {
-    constexpr int64_t kSliceBytes = 4 * W;
-    constexpr int64_t kRowBytes = kRowLanes * kSliceBytes;
+    using P = Pieces<W>;                               // byte copy: rows shared among lanes in 16-byte pieces
+    constexpr int64_t kRowBytes = kRowLanes * 4 * W;
     const int64_t chunk = blockIdx.x % chunks_per_plane;
     const int64_t plane = blockIdx.x / chunks_per_plane;
     const int lane = threadIdx.x % kWaveSize;
@@ -95,14 +95,14 @@ void compact_ragged_kernel(const char* __restrict__ K, const char* __restrict__ 
     }
     Words<W> kr[kRagUnroll], vr[kRagUnroll];
 #pragma unroll
-    for (int u = 0; u < kRagUnroll; ++u) kr[u] = load_words_stream<W>(K + src[u] * kRowBytes + c * kSliceBytes);
+    for (int u = 0; u < kRagUnroll; ++u) kr[u] = load_words_stream<W, P::kStride>(K + src[u] * kRowBytes + c * P::kBytes);
 #pragma unroll
-    for (int u = 0; u < kRagUnroll; ++u) vr[u] = load_words_stream<W>(V + src[u] * kRowBytes + c * kSliceBytes);
+    for (int u = 0; u < kRagUnroll; ++u) vr[u] = load_words_stream<W, P::kStride>(V + src[u] * kRowBytes + c * P::kBytes);
 #pragma unroll
     for (int u = 0; u < kRagUnroll; ++u) {
         if (live[u]) {
-            store_words_stream<W>(Kc + dst[u] * kRowBytes + c * kSliceBytes, kr[u]);
-            store_words_stream<W>(Vc + dst[u] * kRowBytes + c * kSliceBytes, vr[u]);
+            store_words_stream<W, P::kStride>(Kc + dst[u] * kRowBytes + c * P::kBytes, kr[u]);
+            store_words_stream<W, P::kStride>(Vc + dst[u] * kRowBytes + c * P::kBytes, vr[u]);
             if (c == 0) {
                 norms_c[dst[u]] = norms[src[u]];
                 pos_c[dst[u]] = tok[u];
@@ -205,7 +205,7 @@ l2kv_status stream_append_dispatch(const void* Knew, const void* Vnew, l2kv_dtyp
     if (dt == L2KV_F32) {
         if (D == 64) L2KV_APP(F32, 64); else L2KV_APP(F32, 128);
     } else {
-        if (D == 64) L2KV_APP(BF16, 64); else L2KV_APP(BF16, 128);
+        if (D == 64) L2KV_APP(BF16, 64); else if (D == 128) L2KV_APP(BF16, 128); else L2KV_APP(BF16, 256);
     }
 #undef L2KV_APP
     return launch_status();

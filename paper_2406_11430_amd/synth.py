@@ -84,6 +84,10 @@ CONFIGS: Dict[str, CacheConfig] = {
     "C4": CacheConfig("C4-retrieval-131k", 4, L=32, B=1, Hkv=8, Hq=32, D=128,
                       T=131072, dtype="bf16", keep_ratio=0.1, decode_steps=16,
                       span_len=64, span_scale=0.3),
+    # Gemma-7B-shaped MHA stack (16 heads of 256 elements) at its 8k context: an extra
+    # shape for the 512-byte bf16 rows, not one of the contract's workloads.
+    "C6": CacheConfig("C6-gemma-7b-mha-8k", 6, L=28, B=4, Hkv=16, Hq=16, D=256,
+                      T=8192, dtype="bf16", keep_ratio=0.5, decode_steps=64),
 }
 
 

@@ -165,6 +165,8 @@ def test_decode_validation(lib):
     assert call(Hq=7) == E_SHAPE              # not a multiple of Hkv
     assert call(Hq=18) == E_SHAPE             # group of 9 > 8
     assert call(D=80) == E_SHAPE
+    assert call(D=256, stride=25600, dt=0) == E_SHAPE                 # rows of 256 elements: bf16 only,
+    assert call(D=256, stride=25600, Hq=10) == E_SHAPE                # and groups of at most 4 query heads
     assert call(stride=100 * 128 - 1) == E_SHAPE
     assert call(scale=float("nan")) == E_SHAPE
     assert call(ws=None) == E_WS and call(ws_bytes=ws - 1) == E_WS

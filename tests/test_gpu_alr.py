@@ -105,6 +105,7 @@ def rows(rng, shape, dt, scale_rows=True):
     ("f32", 64, 2, 1, 3, 257, 257),
     ("bf16", 128, 1, 1, 5, 1, 1),
     ("bf16", 128, 1, 1, 7, 40000, 20000),
+    ("bf16", 256, 1, 2, 8, 2050, 700),
 ])
 def test_alr_matches_oracle(dev, dt, D, B, Hkv, G, T, m):
     rng = np.random.default_rng(T + G)

@@ -67,7 +67,7 @@ def gpu_decode(Qd, Kd, Vd, n_splits=None, scale=0.0):
 
 
 # ------------------------------------------------------------------- norms
-@pytest.mark.parametrize("dt,D", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128)])
+@pytest.mark.parametrize("dt,D", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128), ("bf16", 256)])
 @pytest.mark.parametrize("T", [1, 7, 127, 128, 129, 1000, 4099])
 def test_norms_bit_exact(dev, dt, D, T):
     rng = np.random.default_rng(T * 131 + D)
@@ -207,7 +207,7 @@ def test_select_by_ratio_entry_point(dev):
 
 
 # -------------------------------------------------------------- compaction
-@pytest.mark.parametrize("dt,D", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128)])
+@pytest.mark.parametrize("dt,D", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128), ("bf16", 256)])
 @pytest.mark.parametrize("T,k", [(1, 1), (70, 1), (70, 63), (70, 64), (70, 65), (1000, 333), (513, 513)])
 def test_compact_bit_exact(dev, dt, D, T, k):
     rng = np.random.default_rng(T * 7 + k)
@@ -239,12 +239,17 @@ def attn_case(rng, B, Hq, Hkv, n, D, dt):
     return Q, K, V
 
 
-@pytest.mark.parametrize("dt,D", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128)])
+@pytest.mark.parametrize("dt,D", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128), ("bf16", 256)])
 @pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_decode_all_group_sizes(dev, dt, D, G):
     rng = np.random.default_rng(G * 17 + D)
     B, Hkv, n = 2, 2, 333
     Q, K, V = attn_case(rng, B, Hkv * G, Hkv, n, D, dt)
+    if D == 256 and G > 4:                    # rows of 256 elements: groups of up to 4 query heads
+        with pytest.raises(l2kv.L2KVError) as e:
+            gpu_decode(to_dev(Q, dt, dev), to_dev(K, dt, dev), to_dev(V, dt, dev))
+        assert e.value.status == -2                # L2KV_ERR_SHAPE
+        return
     want = oracle.decode_attn(Q, K, V, dt)
     got = gpu_decode(to_dev(Q, dt, dev), to_dev(K, dt, dev), to_dev(V, dt, dev)).cpu().numpy()
     err = np.abs(got - want).max()
@@ -267,6 +272,38 @@ def test_decode_ragged_lengths_and_split_counts(dev, n):
         outs.append(got)
     for o in outs[1:]:                       # independent of the split count up to fp32 rounding
         assert np.abs(o - outs[0]).max() <= 5e-5 * max(1.0, np.abs(want).max())
+
+
+@pytest.mark.parametrize("G,n", [(4, 65), (4, 4099), (1, 1000), (3, 16), (2, 9001)])
+def test_decode_rows_of_256_elements(dev, G, n):
+    # bf16 rows of 256 elements (query groups of up to 4 heads): every split count, both builds
+    # of the final merge, and the whole path from the uncompressed cache
+    rng = np.random.default_rng(n + G)
+    B, Hkv, D, dt = 2, 2, 256, "bf16"
+    Q, K, V = attn_case(rng, B, Hkv * G, Hkv, n, D, dt)
+    want = oracle.decode_attn(Q, K, V, dt)
+    Qd, Kd, Vd = to_dev(Q, dt, dev), to_dev(K, dt, dev), to_dev(V, dt, dev)
+    smax = l2kv.l2kv_decode_max_splits(n)
+    for s in sorted({0, 1, 2, 8, 9, smax} & set(range(0, smax + 1))):
+        got = gpu_decode(Qd, Kd, Vd, n_splits=s).cpu().numpy()
+        err = np.abs(got - want).max()
+        assert err <= ATTN_BAR, (n, s, err)
+    # norms -> select -> compact -> decode against the oracle's pipeline
+    k = oracle.keep_count(n, 0.5)
+    n32, _, idx, Kc, Vc = oracle.compress(K.reshape(B * Hkv, n, D), V.reshape(B * Hkv, n, D), dt, 0.5)
+    nd = gpu_norms(Kd.view(B * Hkv, n, D))
+    assert np.array_equal(nd.cpu().numpy().view(np.uint32), n32.view(np.uint32))
+    idd = torch.empty((B * Hkv, k), dtype=torch.int32, device=dev)
+    ws = torch.empty(l2kv.l2kv_select_workspace_bytes(B * Hkv, n), dtype=torch.uint8, device=dev)
+    l2kv.l2kv_select(nd, 0.5, idd, None, ws)
+    assert np.array_equal(idd.cpu().numpy(), idx)
+    Kcd = torch.empty((B * Hkv, k, D), dtype=Kd.dtype, device=dev)
+    Vcd = torch.empty_like(Kcd)
+    l2kv.l2kv_compact(Kd.view(B * Hkv, n, D), Vd.view(B * Hkv, n, D), idd, Kcd, Vcd)
+    assert np.array_equal(synth.as_numpy_bits(Kcd).view(np.uint16), Kc)
+    got = gpu_decode(Qd, Kcd.view(B, Hkv, k, D), Vcd.view(B, Hkv, k, D)).cpu().numpy()
+    want_c = oracle.decode_attn(Q, Kc.reshape(B, Hkv, k, D), Vc.reshape(B, Hkv, k, D), dt)
+    assert np.abs(got - want_c).max() <= ATTN_BAR
 
 
 def test_decode_closed_forms_on_gpu(dev):

@@ -152,7 +152,7 @@ class Batch:
         self.check_cache([min(int(lens_now[s]), budgets[s]) for s in range(self.n_seq)])
 
 
-@pytest.mark.parametrize("dt,D", [("bf16", 128), ("f32", 64)])
+@pytest.mark.parametrize("dt,D", [("bf16", 128), ("f32", 64), ("bf16", 256)])
 def test_stream_growing_budget(dev, dt, D):
     rng = np.random.default_rng(11 + D)
     b = Batch(dev, rng, dt, D, L=2, Hkv=2, G=2, lens=[70, 1, 333, 64, 129], r=0.5, steps=12)

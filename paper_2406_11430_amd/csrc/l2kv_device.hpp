@@ -19,6 +19,8 @@ constexpr int kRowsPerWaveLoad = kWaveSize / kRowLanes;
 // DPP control words (cross-lane operand swizzles inside a 16-lane row).
 constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
 constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppQuadEven = 0xA0;    // quad_perm [0,0,2,2]: every lane reads the even lane of its pair
+constexpr int kDppQuadOdd = 0xF5;     // quad_perm [1,1,3,3]: every lane reads the odd lane of its pair
 constexpr int kDppHalfMirror = 0x141; // lane i <- lane 7-i within 8 lanes
 constexpr int kDppMirror = 0x140;     // lane i <- lane 15-i within 16 lanes
 

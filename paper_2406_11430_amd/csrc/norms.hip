@@ -10,6 +10,14 @@
 // right, then the balanced tree of row16_tree_sum.  Contraction to FMA is
 // switched off so fp32 inputs round product and sum separately, like the stated
 // order says.
+//
+// 512-byte rows (two 16-byte pieces per lane) are loaded with the row shared among
+// the lanes piece by piece (lane c: pieces c and c + 16), which streams better than
+// 32 consecutive bytes per lane.  The fixed order is defined over 32-byte chunks,
+// chunk i = pieces 2i and 2i + 1, so the left-to-right sum of a chunk runs through
+// two neighbouring lanes: the even lane sums its piece, hands the sum to the odd
+// lane, which continues over its own piece; the tree then runs over the odd lanes of
+// each piece slot and the two slots are added last (chunks 0..7 + chunks 8..15).
 #include "l2kv_device.hpp"
 #include "l2kv_host.hpp"
 
@@ -31,6 +39,8 @@ void norms_kernel(const char* __restrict__ K, int64_t T, int64_t head_stride_byt
                   int64_t blocks_per_head, float* __restrict__ norms) {
 #pragma clang fp contract(off)
     using S = Slice<E, D>;
+    using P = Pieces<S::kWords>;
+    static_assert(P::kCount <= 2, "rows of at most 512 bytes");
     const int64_t head = blockIdx.x / blocks_per_head;
     const int64_t chunk = blockIdx.x % blocks_per_head;
     const int lane = threadIdx.x % kWaveSize;
@@ -47,9 +57,9 @@ void norms_kernel(const char* __restrict__ K, int64_t T, int64_t head_stride_byt
     for (int u = 0; u < kNormUnroll; ++u) {
         int64_t row = first + u;
         row = row < T ? row : T - 1;      // tail: re-read the last row, result unused
-        const char* p = head_base + row * S::kRowBytes + c * S::kBytes;
-        if constexpr (kKeep) raw[u] = load_words<S::kWords>(p);
-        else raw[u] = load_words_stream<S::kWords>(p);
+        const char* p = head_base + row * S::kRowBytes + c * P::kBytes;
+        if constexpr (kKeep) raw[u] = load_words<S::kWords, P::kStride>(p);
+        else raw[u] = load_words_stream<S::kWords, P::kStride>(p);
     }
 
     float mine = 0.f;
@@ -57,13 +67,47 @@ void norms_kernel(const char* __restrict__ K, int64_t T, int64_t head_stride_byt
     for (int u = 0; u < kNormUnroll; ++u) {
         float x[S::kElems];
         widen<E, D>(raw[u], x);
-        float acc = x[0] * x[0];
+        float total;
+        if constexpr (P::kCount == 1) {
+            float acc = x[0] * x[0];
 #pragma unroll
-        for (int e = 1; e < S::kElems; ++e) {
-            float sq = x[e] * x[e];
-            acc = acc + sq;
+            for (int e = 1; e < S::kElems; ++e) {
+                float sq = x[e] * x[e];
+                acc = acc + sq;
+            }
+            total = row16_tree_sum(acc);
+        } else {
+            constexpr int n = S::kElems / 2;              // elements per piece; x[s * n ..] = piece slot s
+            float t[2];
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                // first half of a chunk (valid in even lanes): 0 + x0^2 is x0^2 exactly
+                float acc = 0.f;
+#pragma unroll
+                for (int e = 0; e < n; ++e) {
+                    float sq = x[s * n + e] * x[s * n + e];
+                    acc = acc + sq;
+                }
+                // second half (valid in odd lanes): continue from the even neighbour's sum.  Even
+                // lanes continue from their own sum; their result is overwritten below.  (No
+                // select on the lane parity here: the cross-lane read must run with all lanes
+                // active.)
+                float full = dpp_read<kDppQuadEven>(acc);
+#pragma unroll
+                for (int e = 0; e < n; ++e) {
+                    float sq = x[s * n + e] * x[s * n + e];
+                    full = full + sq;
+                }
+                // chunk sums sit in the odd lanes: copy to the even neighbour, then the tree
+                // over the 8 chunks of this slot
+                float v = dpp_read<kDppQuadOdd>(full);
+                v = v + dpp_read<kDppXor2>(v);
+                v = v + dpp_read<kDppHalfMirror>(v);
+                v = v + dpp_read<kDppMirror>(v);
+                t[s] = v;
+            }
+            total = t[0] + t[1];
         }
-        float total = row16_tree_sum(acc);
         mine = (c == u) ? total : mine;   // lane c keeps the sum of row u
     }
     const int64_t row = first + c;

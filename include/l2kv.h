@@ -23,7 +23,8 @@
  *    number of layers / sequences can be flattened into n_heads.
  *  - A K or V row is D contiguous elements; head i starts `head_stride`
  *    ELEMENTS after head i-1 (head_stride >= T*D).  Supported:
- *    D in {64, 128}, dtype in {fp32, bf16}.  Base pointers of K, V, Kc, Vc, Q
+ *    D in {64, 128} for fp32 and bf16, D = 256 for bf16 only (rows of at most
+ *    512 bytes).  Base pointers of K, V, Kc, Vc, Q
  *    must be 16-byte aligned and head_stride*sizeof(elem) a multiple of 16;
  *    norms / index / O / workspace pointers 4-byte aligned (workspace 16).
  *  - Outputs must not alias inputs.
@@ -198,8 +199,8 @@ l2kv_status l2kv_compress(const void* K, const void* V, l2kv_dtype dt, int64_t n
  * Arithmetic: fp32 accumulation throughout; for bf16 caches q.k is formed with
  * the packed bf16 dot instruction (exact bf16 products, fp32 sum), for fp32
  * caches with fp32 FMAs; softmax and the value sum are fp32.
- * Errors: NULL, SHAPE (Hq % Hkv != 0, Hq/Hkv > 8, kv_len <= 0, ...), DTYPE,
- * WORKSPACE, ALIGN, LAUNCH.
+ * Errors: NULL, SHAPE (Hq % Hkv != 0, Hq/Hkv > 8 -- > 4 for D = 256 --,
+ * kv_len <= 0, ...), DTYPE, WORKSPACE, ALIGN, LAUNCH.
  */
 l2kv_status l2kv_decode_attn(const void* Q, const void* Kc, const void* Vc,
                              l2kv_dtype dt, int32_t B, int32_t Hq, int32_t Hkv,

@@ -120,6 +120,19 @@ def test_c4_retrieval_shape_131k(dev):
     torch.cuda.empty_cache()
 
 
+def test_c6_rows_of_256_elements_at_bench_shapes(dev):
+    # bf16 heads of 256 elements (512-byte rows) at the per-launch shapes of the extra bench shape:
+    # 4 of its 28 layers, 16 MHA heads, 8192 tokens, keep 0.5
+    cfg = synth.CONFIGS["C6"].scaled(L=4, decode_steps=2)
+    steps = (0, 1)
+    w = run_workload(cfg, dev, steps)
+    assert w.k == 4096
+    check_properties_all_heads(w)
+    check_sampled_heads(w, [(0, 0, 0), (1, 2, 7), (3, 3, 15)], steps)
+    del w
+    torch.cuda.empty_cache()
+
+
 def test_c5_streaming_batch_sampled_heads(dev):
     # the ragged streaming batch at its real per-launch shapes (64 sequences, prompt lengths
     # 1024..8192, 8 KV / 32 Q heads), 4 of its 32 layers and 24 of its 256 decode steps; the

@@ -109,6 +109,11 @@ __device__ __forceinline__ f32x4 fetch4(__amdgpu_buffer_rsrc_t region, int byte_
     return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(region, byte_offset, 0, kCachePolicySc1));
 }
 
+// 4-byte load with the same policy; voffset per lane, soffset uniform, both in bytes.
+__device__ __forceinline__ float fetch1(__amdgpu_buffer_rsrc_t region, int voffset, int soffset) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(region, voffset, soffset, kCachePolicySc1));
+}
+
 // One output element: fp32, or bf16 (round to nearest even) when the caller asked for it; O then
 // points at 16-bit elements.
 __device__ __forceinline__ void store_out(float* O, int64_t i, float v, int out_bf16) {
@@ -514,16 +519,25 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
     for (int o = threadIdx.x; o < G * D; o += kDecThreads) {
         const int g = o / D;
         const int d = o % D;
+        // all 48 LDS reads first, then the arithmetic: one LDS latency per output element
+        // instead of one per row group
+        float mi[kDecGroups], ai[kDecGroups], li[kDecGroups];
+#pragma unroll
+        for (int i = 0; i < kDecGroups; ++i) {
+            mi[i] = s_m[i * G + g];
+            ai[i] = s_acc[(i * G + g) * D + d];
+            li[i] = s_l[i * G + g];
+        }
+        __builtin_amdgcn_sched_barrier(0);
         float mx = kNegInf;
 #pragma unroll
-        for (int i = 0; i < kDecGroups; ++i) mx = fmaxf(mx, s_m[i * G + g]);
+        for (int i = 0; i < kDecGroups; ++i) mx = fmaxf(mx, mi[i]);
         float num = 0.f, den = 0.f;
 #pragma unroll
         for (int i = 0; i < kDecGroups; ++i) {
-            const float mi = s_m[i * G + g];
-            const float w = mi == kNegInf ? 0.f : fast_exp2(mi - mx);
-            num = fmaf(w, s_acc[(i * G + g) * D + d], num);
-            den = fmaf(w, s_l[i * G + g], den);
+            const float w = mi[i] == kNegInf ? 0.f : fast_exp2(mi[i] - mx);
+            num = fmaf(w, ai[i], num);
+            den = fmaf(w, li[i], den);
         }
         if (n_splits == 1) {
             // the only workgroup of this KV head: its merge is the result (0 for an empty cache)
@@ -571,37 +585,47 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
         // barrier.  (The host never pairs this variant with more than 8 workgroups.)
         constexpr int kOut = (G * D + kDecThreads - 1) / kDecThreads;
         float v[kOut][kNarrow], pm[kOut][kNarrow], pl[kOut][kNarrow];
+        // the partials of this KV head's G query heads are one contiguous region; 32-bit offsets
+        // into it (per lane: query head and element; uniform: workgroup) keep the address
+        // arithmetic off the critical path
+        const __amdgpu_buffer_rsrc_t region = __builtin_amdgcn_make_buffer_rsrc(
+            partial + hq0 * n_splits_grid * kRow, 0, G * n_splits_grid * kRow * (int)sizeof(float), kBufferWord3);
+        const int last = __builtin_amdgcn_readfirstlane(n_splits - 1);
 #pragma unroll
         for (int j = 0; j < kOut; ++j) {
             const int o = threadIdx.x + j * kDecThreads;
             const int oo = o < G * D ? o : 0;                               // idle lanes re-read element 0
-            const int g = oo / D;
-            const int d = oo % D;
+            const int head_off = (oo / D) * n_splits_grid * kRow * (int)sizeof(float);
+            const int elem_off = head_off + (oo % D) * (int)sizeof(float);
+            const int stat_off = head_off + D * (int)sizeof(float);
 #pragma unroll
             for (int i = 0; i < kNarrow; ++i) {
-                const int sp = i < n_splits ? i : n_splits - 1;             // clamp: in bounds, ignored below
-                const float* p = partial + ((hq0 + g) * n_splits_grid + sp) * kRow;
-                v[j][i] = fetch(p + d);
-                pm[j][i] = fetch(p + D);
-                pl[j][i] = fetch(p + D + 1);
+                const int wg_off = (i < last ? i : last) * kRow * (int)sizeof(float);   // clamp: in bounds, weight 0 below
+                v[j][i] = fetch1(region, elem_off, wg_off);
+                pm[j][i] = fetch1(region, stat_off, wg_off);
+                pl[j][i] = fetch1(region, stat_off + 4, wg_off);
             }
         }
+        // every request above is issued before the first use below (the compiler would otherwise
+        // move each load next to its use, behind the branches on the workgroup count, and turn one
+        // memory round trip into several)
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = 0; j < kOut; ++j) {
+            // branch-free: the slots past n_splits hold copies of the last workgroup's values
+            // (finite or -inf like any other) and get weight 0
             float bm = kNegInf;
 #pragma unroll
-            for (int i = 0; i < kNarrow; ++i)
-                if (i < n_splits) bm = fmaxf(bm, pm[j][i]);
+            for (int i = 0; i < kNarrow; ++i) bm = fmaxf(bm, pm[j][i]);
             float num = 0.f, den = 0.f;
 #pragma unroll
             for (int i = 0; i < kNarrow; ++i) {
-                if (i < n_splits) {
-                    // -inf: that workgroup saw no row (cannot happen with the current
-                    // assignment, where every workgroup owns at least one row)
-                    const float w = pm[j][i] == kNegInf ? 0.f : fast_exp2(pm[j][i] - bm);
-                    num = fmaf(w, v[j][i], num);
-                    den = fmaf(w, pl[j][i], den);
-                }
+                // -inf: that workgroup saw no row (cannot happen with the current
+                // assignment, where every workgroup owns at least one row)
+                float w = pm[j][i] == kNegInf ? 0.f : fast_exp2(pm[j][i] - bm);
+                w = i < n_splits ? w : 0.f;
+                num = fmaf(w, v[j][i], num);
+                den = fmaf(w, pl[j][i], den);
             }
             const int o = threadIdx.x + j * kDecThreads;
             if (o < G * D) store_out(O, hq0 * D + o, den > 0.f ? num / den : 0.f, out_bf16);   // 0 for an empty cache

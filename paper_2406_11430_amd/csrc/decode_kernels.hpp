@@ -214,6 +214,8 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
     constexpr int kLdsFloats = kAccFloats + 2 * kDecGroups * G > kTabFloats ? kAccFloats + 2 * kDecGroups * G : kTabFloats;
     __shared__ __attribute__((aligned(16))) float s_raw[kLdsFloats];
     __shared__ uint32_t s_ticket;
+    __shared__ float s_max[G];                   // per query head: maximum of the workgroups' m (final merge)
+    if (threadIdx.x < G) s_max[threadIdx.x] = -INFINITY;       // ordered before its use by the barriers below
     float* const s_acc = s_raw;                                          // [(grp * G + g) * D + d]
     float* const s_m = s_raw + kAccFloats;                               // [grp * G + g]
     float* const s_l = s_m + kDecGroups * G;
@@ -631,27 +633,29 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
             if (o < G * D) store_out(O, hq0 * D + o, den > 0.f ? num / den : 0.f, out_bf16);   // 0 for an empty cache
         }
     } else {
-    // Launches with more than 8 workgroups per KV head: final merge in one memory round trip.  The weights depend on (m, l) only,
-    // the sums on the accumulators only, so both are requested at once.  The
-    // (m, l) of every (query head, workgroup) go to LDS, where the per-head
-    // maximum and the weights w = 2^(m - max), w*l are formed once.  The
-    // accumulators come in as 16-byte pieces: piece q = (g, 4 consecutive d)
-    // is shared by kWays threads, thread `way` taking the workgroups way,
-    // way + kWays, ...; the kWays partial sums meet in LDS and are added in
-    // order of `way`, so the result does not depend on timing.
+    // Launches with more than 8 workgroups per KV head: final merge in one memory round trip
+    // and four LDS steps.  The weights depend on (m, l) only, the sums on the accumulators
+    // only, so both are requested at once.  Entry e = (workgroup, query head) is handled by
+    // thread e % 256: (1) an LDS float-max per head (order-free, hence bit-reproducible) gives
+    // the per-head maximum; (2) w = 2^(m - max) and w*l go to LDS tables; (3) the accumulators,
+    // which arrived as 16-byte pieces -- piece q = (g, 4 consecutive d) is shared by kWays
+    // threads, thread `way` taking the workgroups way, way + kWays, ... -- are weighted and
+    // summed, together with the w*l of the same workgroups; (4) the kWays partial sums meet in
+    // LDS and are added in order of `way`, so the result does not depend on timing.
     {
         constexpr int kBatch = 16;                                       // 16-byte loads in flight per thread
         constexpr int kEnt = (G * kDecodeMaxSplits + kDecThreads - 1) / kDecThreads;
-        float* const s_pm = s_raw;                                       // [G][n_splits] maxima
-        float* const s_w = s_pm + G * kDecodeMaxSplits;                  // [G][n_splits] weights
+        float* const s_w = s_raw;                                        // [G][n_splits] weights
         float* const s_wl = s_w + G * kDecodeMaxSplits;                  // [G][n_splits] weights * l
         float* const s_red = s_wl + G * kDecodeMaxSplits;                // [kWays][G * D] partial sums
+        float* const s_den = s_red + kWays * G * D;                      // [kWays][G] partial denominators
+        static_assert(2 * G * kDecodeMaxSplits + kWays * G * D + kWays * G <= kLdsFloats, "LDS tables");
         const int n_ent = G * n_splits;
         const bool active = (int)threadIdx.x < kWays * kQuads;
         const int way = active ? (int)threadIdx.x / kQuads : 0;
         const int q = active ? (int)threadIdx.x % kQuads : 0;
         const int qg = q / (D / 4);
-        // the accumulators of this KV head's G query heads are one contiguous region
+        // the partials of this KV head's G query heads are one contiguous region
         const __amdgpu_buffer_rsrc_t region = __builtin_amdgcn_make_buffer_rsrc(
             partial + hq0 * n_splits_grid * kRow, 0, G * n_splits_grid * kRow * (int)sizeof(float), kBufferWord3);
         const int q_off = (qg * n_splits_grid * kRow + (q % (D / 4)) * 4) * (int)sizeof(float);
@@ -666,43 +670,33 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
         for (int t = 0; t < kEnt; ++t) {
             const int e = threadIdx.x + t * kDecThreads;
             const int ee = e < n_ent ? e : 0;
-            const float* p = partial + ((hq0 + ee / n_splits) * n_splits_grid + ee % n_splits) * kRow;
-            pm[t] = fetch(p + D);
-            pl[t] = fetch(p + D + 1);
+            const int stat_off = (((ee % G) * n_splits_grid + ee / G) * kRow + D) * (int)sizeof(float);
+            pm[t] = fetch1(region, stat_off, 0);
+            pl[t] = fetch1(region, stat_off + 4, 0);
         }
         // keep every request above ahead of the LDS work below (the compiler would otherwise
-        // sink the accumulator loads behind the two barriers, next to their first use)
+        // sink the accumulator loads behind the barriers, next to their first use)
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int t = 0; t < kEnt; ++t) {
             const int e = threadIdx.x + t * kDecThreads;
-            if (e < n_ent) s_pm[e] = pm[t];
+            if (e < n_ent) __hip_atomic_fetch_max(&s_max[e % G], pm[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         }
         __syncthreads();
 #pragma unroll
         for (int t = 0; t < kEnt; ++t) {
             const int e = threadIdx.x + t * kDecThreads;
             if (e < n_ent) {
-                // LDS reads in independent batches of 8 (clamped index, the clamped
-                // duplicates do not change a maximum): one wait per batch, not per read
-                const float* row = s_pm + (e / n_splits) * n_splits;
-                float bm = kNegInf;
-                for (int i0 = 0; i0 < n_splits; i0 += 8) {
-                    float r[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) r[i] = row[i0 + i < n_splits ? i0 + i : n_splits - 1];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) bm = fmaxf(bm, r[i]);
-                }
                 // -inf: that workgroup saw no row (cannot happen with the current
                 // assignment, where every workgroup owns at least one row)
-                const float w = pm[t] == kNegInf ? 0.f : fast_exp2(pm[t] - bm);
-                s_w[e] = w;
-                s_wl[e] = w * pl[t];
+                const float w = pm[t] == kNegInf ? 0.f : fast_exp2(pm[t] - s_max[e % G]);
+                s_w[(e % G) * n_splits + e / G] = w;
+                s_wl[(e % G) * n_splits + e / G] = w * pl[t];
             }
         }
         __syncthreads();
         f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+        float dsum = 0.f;
         for (int s0 = 0; s0 < n_splits; s0 += kBatch * kWays) {
             if (s0 > 0) {
 #pragma unroll
@@ -711,35 +705,36 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
                     v[i] = fetch4(region, q_off + (sp < n_splits ? sp : n_splits - 1) * kRow * (int)sizeof(float));
                 }
             }
-            float w[kBatch];                                              // independent LDS reads first
+            float w[kBatch], wl[kBatch];                                  // independent LDS reads first
 #pragma unroll
             for (int i = 0; i < kBatch; ++i) {
                 const int sp = s0 + way + i * kWays;
                 w[i] = s_w[qg * n_splits + (sp < n_splits ? sp : n_splits - 1)];
+                wl[i] = s_wl[qg * n_splits + (sp < n_splits ? sp : n_splits - 1)];
             }
 #pragma unroll
             for (int i = 0; i < kBatch; ++i) {
-                if (s0 + way + i * kWays < n_splits) {
-                    sum.x = fmaf(w[i], v[i].x, sum.x);
-                    sum.y = fmaf(w[i], v[i].y, sum.y);
-                    sum.z = fmaf(w[i], v[i].z, sum.z);
-                    sum.w = fmaf(w[i], v[i].w, sum.w);
-                }
+                const bool live = s0 + way + i * kWays < n_splits;
+                const float wi = live ? w[i] : 0.f;
+                sum.x = fmaf(wi, v[i].x, sum.x);
+                sum.y = fmaf(wi, v[i].y, sum.y);
+                sum.z = fmaf(wi, v[i].z, sum.z);
+                sum.w = fmaf(wi, v[i].w, sum.w);
+                dsum += live ? wl[i] : 0.f;
             }
         }
-        if (active) *reinterpret_cast<f32x4*>(s_red + way * (G * D) + q * 4) = sum;
+        if (active) {
+            *reinterpret_cast<f32x4*>(s_red + way * (G * D) + q * 4) = sum;
+            if (q % (D / 4) == 0) s_den[way * G + qg] = dsum;
+        }
         __syncthreads();
         for (int o = threadIdx.x; o < G * D; o += kDecThreads) {
             const int g = o / D;
             float num = 0.f, den = 0.f;
 #pragma unroll
-            for (int y = 0; y < kWays; ++y) num += s_red[y * (G * D) + o];
-            for (int i0 = 0; i0 < n_splits; i0 += 8) {
-                float r[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) r[i] = s_wl[g * n_splits + (i0 + i < n_splits ? i0 + i : n_splits - 1)];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) den += i0 + i < n_splits ? r[i] : 0.f;
+            for (int y = 0; y < kWays; ++y) {
+                num += s_red[y * (G * D) + o];
+                den += s_den[y * G + g];
             }
             store_out(O, hq0 * D + o, den > 0.f ? num / den : 0.f, out_bf16);   // 0 for an empty cache
         }

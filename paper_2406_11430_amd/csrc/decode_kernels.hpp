@@ -109,7 +109,11 @@ __device__ __forceinline__ f32x4 fetch4(__amdgpu_buffer_rsrc_t region, int byte_
     return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(region, byte_offset, 0, kCachePolicySc1));
 }
 
-// 4-byte load with the same policy; voffset per lane, soffset uniform, both in bytes.
+// 8-byte and 4-byte loads with the same policy; voffset per lane, soffset uniform, both in bytes.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ f32x2 fetch2(__amdgpu_buffer_rsrc_t region, int voffset, int soffset) {
+    return __builtin_bit_cast(f32x2, __builtin_amdgcn_raw_buffer_load_b64(region, voffset, soffset, kCachePolicySc1));
+}
 __device__ __forceinline__ float fetch1(__amdgpu_buffer_rsrc_t region, int voffset, int soffset) {
     return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(region, voffset, soffset, kCachePolicySc1));
 }
@@ -518,38 +522,57 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
         }
     }
     __syncthreads();
-    for (int o = threadIdx.x; o < G * D; o += kDecThreads) {
-        const int g = o / D;
-        const int d = o % D;
-        // all 48 LDS reads first, then the arithmetic: one LDS latency per output element
-        // instead of one per row group
-        float mi[kDecGroups], ai[kDecGroups], li[kDecGroups];
+    // Thread t forms the kVec consecutive output elements t * kVec .. of the G * D (all of one
+    // query head): the weights of the 16 row groups are computed once per thread, and all LDS
+    // reads are issued before the arithmetic (one LDS latency, not one per row group).
+    constexpr int kVec = G * D <= kDecThreads ? 1 : (G * D <= 2 * kDecThreads ? 2 : 4);
+    static_assert(G * D <= 4 * kDecThreads && D % kVec == 0, "output elements per thread");
+    const int o0 = threadIdx.x * kVec;
+    if (o0 < G * D) {
+        const int g = o0 / D;
+        const int d = o0 % D;
+        float mi[kDecGroups], li[kDecGroups], ai[kDecGroups][kVec];
 #pragma unroll
         for (int i = 0; i < kDecGroups; ++i) {
             mi[i] = s_m[i * G + g];
-            ai[i] = s_acc[(i * G + g) * D + d];
             li[i] = s_l[i * G + g];
+            const float* a = s_acc + (i * G + g) * D + d;
+            if constexpr (kVec == 4) {
+                const f32x4 t = *reinterpret_cast<const f32x4*>(a);
+                ai[i][0] = t.x; ai[i][1] = t.y; ai[i][2] = t.z; ai[i][3] = t.w;
+            } else if constexpr (kVec == 2) {
+                const f32x2 t = *reinterpret_cast<const f32x2*>(a);
+                ai[i][0] = t.x; ai[i][1] = t.y;
+            } else {
+                ai[i][0] = a[0];
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
         float mx = kNegInf;
 #pragma unroll
         for (int i = 0; i < kDecGroups; ++i) mx = fmaxf(mx, mi[i]);
-        float num = 0.f, den = 0.f;
+        float num[kVec], den = 0.f;
+#pragma unroll
+        for (int k = 0; k < kVec; ++k) num[k] = 0.f;
 #pragma unroll
         for (int i = 0; i < kDecGroups; ++i) {
             const float w = mi[i] == kNegInf ? 0.f : fast_exp2(mi[i] - mx);
-            num = fmaf(w, ai[i], num);
+#pragma unroll
+            for (int k = 0; k < kVec; ++k) num[k] = fmaf(w, ai[i][k], num[k]);
             den = fmaf(w, li[i], den);
         }
         if (n_splits == 1) {
             // the only workgroup of this KV head: its merge is the result (0 for an empty cache)
-            store_out(O, hq0 * D + o, den > 0.f ? num / den : 0.f, out_bf16);
+#pragma unroll
+            for (int k = 0; k < kVec; ++k)
+                store_out(O, hq0 * D + o0 + k, den > 0.f ? num[k] / den : 0.f, out_bf16);
         } else {
             // Device-scope stores: written through to the level every compute unit
             // of the device reads from, so the merging workgroup below sees them
             // without any bulk cache write-back.
             float* out = partial + ((hq0 + g) * n_splits_grid + split) * kRow;
-            publish(out + d, num);
+#pragma unroll
+            for (int k = 0; k < kVec; ++k) publish(out + d + k, num[k]);
             if (d == 0) {
                 publish(out + D, mx);
                 publish(out + D + 1, den);
@@ -581,56 +604,62 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
 
     constexpr int kNarrow = 8;
     if constexpr (!kWideMerge) {
-        // Launches with at most 8 workgroups per KV head: every lane fetches, for each of its
-        // output elements (g, d), the accumulator element together with (m, l) of all
-        // workgroups at once: all loads are independent, one memory round trip, no LDS, no
-        // barrier.  (The host never pairs this variant with more than 8 workgroups.)
-        constexpr int kOut = (G * D + kDecThreads - 1) / kDecThreads;
-        float v[kOut][kNarrow], pm[kOut][kNarrow], pl[kOut][kNarrow];
-        // the partials of this KV head's G query heads are one contiguous region; 32-bit offsets
-        // into it (per lane: query head and element; uniform: workgroup) keep the address
-        // arithmetic off the critical path
+        // Launches with at most 8 workgroups per KV head: every lane fetches, for its kVec
+        // output elements (one query head, consecutive d), the accumulator elements together
+        // with (m, l) of all workgroups at once: all loads are independent, one memory round
+        // trip, no LDS, no barrier.  (The host never pairs this variant with more than 8
+        // workgroups.)  The partials of this KV head's G query heads are one contiguous region;
+        // 32-bit offsets into it (per lane: query head and element; uniform: workgroup) keep the
+        // address arithmetic off the critical path.
         const __amdgpu_buffer_rsrc_t region = __builtin_amdgcn_make_buffer_rsrc(
             partial + hq0 * n_splits_grid * kRow, 0, G * n_splits_grid * kRow * (int)sizeof(float), kBufferWord3);
         const int last = __builtin_amdgcn_readfirstlane(n_splits - 1);
+        const int oo = o0 < G * D ? o0 : 0;                                 // idle lanes re-read element 0
+        const int head_off = (oo / D) * n_splits_grid * kRow * (int)sizeof(float);
+        const int elem_off = head_off + (oo % D) * (int)sizeof(float);
+        const int stat_off = head_off + D * (int)sizeof(float);
+        float v[kNarrow][kVec], pm[kNarrow], pl[kNarrow];
 #pragma unroll
-        for (int j = 0; j < kOut; ++j) {
-            const int o = threadIdx.x + j * kDecThreads;
-            const int oo = o < G * D ? o : 0;                               // idle lanes re-read element 0
-            const int head_off = (oo / D) * n_splits_grid * kRow * (int)sizeof(float);
-            const int elem_off = head_off + (oo % D) * (int)sizeof(float);
-            const int stat_off = head_off + D * (int)sizeof(float);
-#pragma unroll
-            for (int i = 0; i < kNarrow; ++i) {
-                const int wg_off = (i < last ? i : last) * kRow * (int)sizeof(float);   // clamp: in bounds, weight 0 below
-                v[j][i] = fetch1(region, elem_off, wg_off);
-                pm[j][i] = fetch1(region, stat_off, wg_off);
-                pl[j][i] = fetch1(region, stat_off + 4, wg_off);
+        for (int i = 0; i < kNarrow; ++i) {
+            const int wg_off = (i < last ? i : last) * kRow * (int)sizeof(float);   // clamp: in bounds, weight 0 below
+            if constexpr (kVec == 4) {
+                const f32x4 t = fetch4(region, elem_off + wg_off);
+                v[i][0] = t.x; v[i][1] = t.y; v[i][2] = t.z; v[i][3] = t.w;
+            } else if constexpr (kVec == 2) {
+                const f32x2 t = fetch2(region, elem_off, wg_off);
+                v[i][0] = t.x; v[i][1] = t.y;
+            } else {
+                v[i][0] = fetch1(region, elem_off, wg_off);
             }
+            const f32x2 st = fetch2(region, stat_off, wg_off);
+            pm[i] = st.x;
+            pl[i] = st.y;
         }
         // every request above is issued before the first use below (the compiler would otherwise
-        // move each load next to its use, behind the branches on the workgroup count, and turn one
-        // memory round trip into several)
+        // move each load next to its use and turn one memory round trip into several)
         __builtin_amdgcn_sched_barrier(0);
+        // branch-free: the slots past n_splits hold copies of the last workgroup's values
+        // (finite or -inf like any other) and get weight 0
+        float bm = kNegInf;
 #pragma unroll
-        for (int j = 0; j < kOut; ++j) {
-            // branch-free: the slots past n_splits hold copies of the last workgroup's values
-            // (finite or -inf like any other) and get weight 0
-            float bm = kNegInf;
+        for (int i = 0; i < kNarrow; ++i) bm = fmaxf(bm, pm[i]);
+        float num[kVec], den = 0.f;
 #pragma unroll
-            for (int i = 0; i < kNarrow; ++i) bm = fmaxf(bm, pm[j][i]);
-            float num = 0.f, den = 0.f;
+        for (int k = 0; k < kVec; ++k) num[k] = 0.f;
 #pragma unroll
-            for (int i = 0; i < kNarrow; ++i) {
-                // -inf: that workgroup saw no row (cannot happen with the current
-                // assignment, where every workgroup owns at least one row)
-                float w = pm[j][i] == kNegInf ? 0.f : fast_exp2(pm[j][i] - bm);
-                w = i < n_splits ? w : 0.f;
-                num = fmaf(w, v[j][i], num);
-                den = fmaf(w, pl[j][i], den);
-            }
-            const int o = threadIdx.x + j * kDecThreads;
-            if (o < G * D) store_out(O, hq0 * D + o, den > 0.f ? num / den : 0.f, out_bf16);   // 0 for an empty cache
+        for (int i = 0; i < kNarrow; ++i) {
+            // -inf: that workgroup saw no row (cannot happen with the current
+            // assignment, where every workgroup owns at least one row)
+            float w = pm[i] == kNegInf ? 0.f : fast_exp2(pm[i] - bm);
+            w = i < n_splits ? w : 0.f;
+#pragma unroll
+            for (int k = 0; k < kVec; ++k) num[k] = fmaf(w, v[i][k], num[k]);
+            den = fmaf(w, pl[i], den);
+        }
+        if (o0 < G * D) {
+#pragma unroll
+            for (int k = 0; k < kVec; ++k)
+                store_out(O, hq0 * D + o0 + k, den > 0.f ? num[k] / den : 0.f, out_bf16);   // 0 for an empty cache
         }
     } else {
     // Launches with more than 8 workgroups per KV head: final merge in one memory round trip

@@ -19,8 +19,9 @@
 // (both operands are exact bf16 inputs); the softmax scale is applied to the
 // fp32 score afterwards.  fp32 caches use plain fp32 FMAs.
 //
-// Query groups of 7 and 8 heads (bf16, D = 128) form q.k on the matrix unit
-// instead and run the softmax once per (head, row); see decode_item.
+// Query groups of 6 to 8 heads (bf16, D = 128) form q.k on the matrix unit
+// instead, run the softmax once per (head, row) and, in grid launches, form p.V
+// on the matrix unit in fp32; see decode_item.
 //
 // At the end the 16 row groups of the workgroup are merged through LDS.  A KV
 // head with a single workgroup writes O from that merge.  Otherwise one partial
@@ -184,6 +185,16 @@ __device__ __forceinline__ void load_tile_clamped(Tile<E, D>& t, const char* Kh,
     for (int u = 0; u < kDecLoads; ++u) t.v[u] = stream_words<S::kWords>(Vh + off[u]);
 }
 
+// The builds that use the matrix unit (bf16, D = 128, 6 to 8 query heads per KV head) state an
+// occupancy of at least 2 waves per SIMD: a wave may then use at most 256 registers, all of them
+// ordinary vector registers, and the compiler keeps the accumulators of the matrix instructions
+// in vector registers, where the rescaling of the online softmax reaches them without copies from
+// and to the accumulation registers.
+template <typename E, int D, int G>
+constexpr bool kDecodeOnMatrixUnit = E::kBytes == 2 && D == 128 && G >= 6;
+template <typename E, int D, int G>
+constexpr int kDecodeMinWaves = kDecodeOnMatrixUnit<E, D, G> ? 2 : 1;
+
 // workspace layout: [counters + work queue: decode_counter_bytes] [partials]
 // partials: [B*Hq][n_splits][D + 4] floats: acc[0..D), m (log2 domain), l, two floats of padding
 // (rows start on 16-byte boundaries; no two workgroups write into the same row).
@@ -194,7 +205,7 @@ __device__ __forceinline__ void load_tile_clamped(Tile<E, D>& t, const char* Kh,
 // With n_splits == 1 the workgroup's own merge already is the result.
 // Called by all threads of the workgroup; every barrier below is reached by all
 // of them or by none (the conditions are uniform).
-template <typename E, int D, int G, bool kWideMerge>
+template <typename E, int D, int G, bool kWideMerge, bool kGridLaunch>
 __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const char* __restrict__ Kh,
                                             const char* __restrict__ Vh, int64_t kv_len, int64_t hq0,
                                             int split, int n_splits, int n_splits_grid,
@@ -255,31 +266,39 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
         for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
     }
 
-    // ---- query groups of 7 and 8 heads (bf16, D = 128): q.k on the matrix unit --------------
-    // With that many heads per streamed row the vector ALU, not HBM, bounds the launch (a wave
-    // spends 80 % of its time issuing vector instructions already at 4 heads), and S = Q.K^T is a
-    // real contraction: M = heads (padded to 16), N = the 16 rows of a tile, K = 128.  Measured
-    // per C3-shaped layer launch, vector path / this path: 5 heads 47.2 / 49.2 us, 6 heads
-    // 48.7 / 49.7, 7 heads 55.0 / 50.9, 8 heads 61.3 / 52.2 -- hence the threshold.  The K tile
+    // ---- query groups of 6 to 8 heads (bf16, D = 128): q.k on the matrix unit ----------------
+    // With that many heads per streamed row the vector ALU, not HBM, bounds the launch, and
+    // S = Q.K^T is a real contraction: M = heads (padded to 16), N = the 16 rows of a tile,
+    // K = 128.  Measured per C3-shaped layer launch, vector path / this path (with p.V on the
+    // matrix unit too, below): 5 heads 45.4 / 45.8 us, 6 heads 47.4 / 46.1, 7 heads 47.7 / 46.0,
+    // 8 heads 49.1 / 46.0 -- hence the threshold.  The K tile
     // goes through a wave-private LDS buffer into the operand layout of
     // v_mfma_f32_16x16x32_bf16 (lane (c, rg) supplies row c, elements 32j + 8rg .. +7 for
     // j = 0..3); the result has heads 4rg .. 4rg+3 of row c in lane (c, rg), where the online
     // softmax runs ONCE per (head, row) instead of in all 16 lanes of a row group; the weights
     // and the rescaling factors return through LDS to the row-per-16-lanes layout in which V
-    // was loaded, and p.V stays on the fp32 vector unit (bf16 weights would cost 2e-3 relative).
+    // was loaded, where p.V is formed in fp32 (bf16 weights would cost 2e-3 relative).
     // All four row groups of a wave share one running maximum per head.  (Loading K straight
     // into the operand layout -- 64 contiguous bytes of each of 16 rows per load instruction
     // instead of 256 bytes of each of 4 rows -- needs no LDS staging but streams worse: 59.1 us
     // against 52.6 us at 8 heads.)
-    constexpr bool kMfma = kBf16 && D == 128 && G >= 7;
-    __shared__ __attribute__((aligned(16))) char s_ktile[kMfma ? kDecWaves * 16 * kKtRow : 16];
-    __shared__ __attribute__((aligned(16))) float s_pw[kMfma ? kDecWaves * G * 16 : 4];
-    __shared__ __attribute__((aligned(16))) float s_aw[kMfma ? kDecWaves * 8 : 4];
+    constexpr bool kMfma = kDecodeOnMatrixUnit<E, D, G>;
+    // p.V on the matrix unit as well: grid launches only.  The work-list kernel carries more
+    // live state and would spill under the 256-register budget this needs (measured on the
+    // ragged streaming batch at 8 heads per group: 126 us per layer with the spills, 112 us with
+    // the accumulators in accumulation registers, 108 us with p.V on the vector unit).
+    constexpr bool kPvMatrix = kMfma && kGridLaunch;
+    // The wave-private buffers of this path (K tile, weights, rescaling factors) live in the
+    // LDS array that the merge after the loop uses: the workgroup then needs less than half of a
+    // compute unit's LDS, two workgroups fit, and the occupancy stated for these builds holds.
+    constexpr int kKtFloats = kDecWaves * 16 * kKtRow / 4;
+    static_assert(!kMfma || kKtFloats + kDecWaves * G * 16 + kDecWaves * 8 <= kLdsFloats, "loop buffers exceed the merge array");
     [[maybe_unused]] bf16x8_t qa[4];                     // matrix operand of Q: head c, elements 32j + 8rg ..
     [[maybe_unused]] float cm[4], cl[4];                 // heads 4rg+i: running maximum (raw), denominator of row position c
-    [[maybe_unused]] char* const kt = s_ktile + (kMfma ? wave * 16 * kKtRow : 0);
-    [[maybe_unused]] float* const sp = s_pw + (kMfma ? wave * G * 16 : 0);
-    [[maybe_unused]] float* const sa = s_aw + (kMfma ? wave * 8 : 0);
+    [[maybe_unused]] f32x4 accq0[kPvMatrix ? EPL : 1], accq1[kPvMatrix ? EPL : 1];   // per element: heads 0..3, heads 4..7
+    [[maybe_unused]] char* const kt = reinterpret_cast<char*>(s_raw) + (kMfma ? wave * 16 * kKtRow : 0);
+    [[maybe_unused]] float* const sp = s_raw + (kMfma ? kKtFloats + wave * G * 16 : 0);
+    [[maybe_unused]] float* const sa = s_raw + (kMfma ? kKtFloats + kDecWaves * G * 16 + wave * 8 : 0);
     if constexpr (kMfma) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -292,6 +311,13 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
         for (int i = 0; i < 4; ++i) {
             cm[i] = kNegInf;
             cl[i] = 0.f;
+        }
+        if constexpr (kPvMatrix) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                accq0[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+                accq1[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
         }
     }
     auto consume_mfma = [&](const Tile<E, D>& t, int64_t first_row, bool ragged) {
@@ -331,25 +357,57 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
             }
             __builtin_amdgcn_wave_barrier();
             // 4. p.V in the layout V was loaded in: lane (rg, c) holds rows 4u + rg, elements 8c ..
-            float al[G], pw[G][kDecLoads];
+            float al[G];
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                al[g] = sa[g];
-                const f32x4 pg = *reinterpret_cast<const f32x4*>(sp + g * 16 + rg * 4);
-                pw[g][0] = pg.x; pw[g][1] = pg.y; pw[g][2] = pg.z; pw[g][3] = pg.w;
-            }
+            for (int g = 0; g < G; ++g) al[g] = sa[g];
+            if constexpr (kPvMatrix) {
+                // On the matrix unit in fp32: v_mfma_f32_4x4x1_16b_f32 computes, per lane l and
+                // result register r, D[r] += A(lane 4*(l/4) + r) * B(lane l).  With B = one value
+                // element of this lane and A = the weight of head (lane % 4) [+ 4], one
+                // instruction is the multiply-add of four heads, and it runs beside the vector
+                // unit.
+                const int ga = c % 4;
+                const f32x4 pa = *reinterpret_cast<const f32x4*>(sp + ga * 16 + rg * 4);           // heads 0..3
+                f32x4 pb = {0.f, 0.f, 0.f, 0.f};                                                 // heads 4..7
+                if (ga + 4 < G) pb = *reinterpret_cast<const f32x4*>(sp + (ga + 4) * 16 + rg * 4);
 #pragma unroll
-            for (int g = 0; g < G; ++g)
+                for (int e = 0; e < EPL; ++e) {
+                    accq0[e].x *= al[0]; accq0[e].y *= al[1]; accq0[e].z *= al[2]; accq0[e].w *= al[3];
+                    if constexpr (G > 4) accq1[e].x *= al[4];
+                    if constexpr (G > 5) accq1[e].y *= al[5];
+                    if constexpr (G > 6) accq1[e].z *= al[6];
+                    if constexpr (G > 7) accq1[e].w *= al[7];
+                }
 #pragma unroll
-                for (int e = 0; e < EPL; ++e) acc[g][e] *= al[g];
+                for (int u = 0; u < kDecLoads; ++u) {
+                    float vx[EPL];
+                    widen<E, D>(t.v[u], vx);
 #pragma unroll
-            for (int u = 0; u < kDecLoads; ++u) {
-                float vx[EPL];
-                widen<E, D>(t.v[u], vx);
+                    for (int e = 0; e < EPL; ++e) {
+                        accq0[e] = __builtin_amdgcn_mfma_f32_4x4x1f32(pa[u], vx[e], accq0[e], 0, 0, 0);
+                        accq1[e] = __builtin_amdgcn_mfma_f32_4x4x1f32(pb[u], vx[e], accq1[e], 0, 0, 0);
+                    }
+                }
+            } else {
+                float pw[G][kDecLoads];
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    const f32x4 pg = *reinterpret_cast<const f32x4*>(sp + g * 16 + rg * 4);
+                    pw[g][0] = pg.x; pw[g][1] = pg.y; pw[g][2] = pg.z; pw[g][3] = pg.w;
+                }
 #pragma unroll
                 for (int g = 0; g < G; ++g)
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(pw[g][u], vx[e], acc[g][e]);
+                    for (int e = 0; e < EPL; ++e) acc[g][e] *= al[g];
+#pragma unroll
+                for (int u = 0; u < kDecLoads; ++u) {
+                    float vx[EPL];
+                    widen<E, D>(t.v[u], vx);
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(pw[g][u], vx[e], acc[g][e]);
+                }
             }
             __builtin_amdgcn_wave_barrier();          // the buffers are rewritten by the next tile
         }
@@ -501,6 +559,10 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
         for (int g = 0; g < G; ++g) {
             m[g] = sa[g];
             l[g] = rg == 0 ? sp[g] : 0.f;
+            if constexpr (kPvMatrix) {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[g][e] = g < 4 ? accq0[e][g] : accq1[e][g - 4];
+            }
         }
     }
 
@@ -511,6 +573,7 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
         drawn = gridDim.x + __hip_atomic_fetch_add(queue, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
     // ---- merge the 16 row groups of the workgroup through LDS --------------
+    if constexpr (kMfma) __syncthreads();          // every wave is done with its buffers in that array
     const int grp = wave * kRowsPerWaveLoad + rg;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -777,7 +840,7 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
 // Grid launch: blockIdx.x = share of the KV head, blockIdx.y = (sequence or
 // position in the launch order) x KV head.
 template <typename E, int D, int G, bool kWideMerge>
-__global__ __launch_bounds__(kDecThreads)
+__global__ __launch_bounds__(kDecThreads) __attribute__((amdgpu_waves_per_eu(kDecodeMinWaves<E, D, G>)))
 void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
                    const char* __restrict__ Vc, int Hkv, int64_t kv_len_uniform,
                    int64_t head_stride_bytes, const int32_t* __restrict__ lens,
@@ -821,8 +884,8 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
         if (split >= n_splits) return;
     }
     uint32_t unused = 0;
-    decode_item<E, D, G, kWideMerge>(Q, Kc + slab, Vc + slab, kv_len, hq0, split, n_splits, n_splits_grid,
-                                     scale_log2e, counters + ((int64_t)b * Hkv + hkv), partial, O, out_bf16, nullptr, unused);
+    decode_item<E, D, G, kWideMerge, true>(Q, Kc + slab, Vc + slab, kv_len, hq0, split, n_splits, n_splits_grid,
+                                           scale_log2e, counters + ((int64_t)b * Hkv + hkv), partial, O, out_bf16, nullptr, unused);
 }
 
 // Work-list launch for ragged batches with a known longest-first order.  A
@@ -875,8 +938,8 @@ void decode_worklist_kernel(const char* __restrict__ Q, const char* __restrict__
             continue;
         }
         const int64_t hq0 = (int64_t)b * Hq + (int64_t)hkv * G;
-        decode_item<E, D, G, kWideMerge>(Q, Kc + slab, Vc + slab, kv_len, hq0, split, n_splits, n_splits_grid,
-                                         scale_log2e, counters + ((int64_t)b * Hkv + hkv), partial, O, out_bf16, &queue[0], drawn);
+        decode_item<E, D, G, kWideMerge, false>(Q, Kc + slab, Vc + slab, kv_len, hq0, split, n_splits, n_splits_grid,
+                                                scale_log2e, counters + ((int64_t)b * Hkv + hkv), partial, O, out_bf16, &queue[0], drawn);
     }
     if (threadIdx.x == 0) {
         // every draw of this workgroup has returned (its value was used above), so the workgroup

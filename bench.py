@@ -471,6 +471,59 @@ def main_stream(args, dev):
     print(json.dumps(out))
 
 
+def main_placement(args, dev):
+    """Where the cache lies in device memory changes what the memory system delivers.  This probe
+    (not a benchmark line) fills the memory with 1 GiB cache tensors in allocation order and
+    reports, per position: the read rate of the norm pass, and the time of a C3-shaped decode
+    launch (8 layers, B=4, 8 KV / 32 Q heads, 16384 rows, bf16) whose K and V are neighbours or a
+    given number of GiB apart."""
+    L, B, Hkv, Hq, n, D = 8, 4, 8, 32, 16384, 128
+    dt = torch.bfloat16
+    tensor_bytes = L * B * Hkv * n * D * 2                                  # 1 GiB
+    Q = torch.randn((L, B, Hq, D), device=dev, dtype=dt)
+    O = torch.empty((L, B, Hq, D), device=dev, dtype=torch.float32)
+    ws = torch.zeros(l2kv.l2kv_decode_workspace_bytes(B, Hq, n, D), dtype=torch.uint8, device=dev)
+    norms = torch.empty((L, B, Hkv, n), dtype=torch.float32, device=dev)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps                                      # ms
+
+    def decode_us(Kc, Vc):
+        def run():
+            for layer in range(L):
+                l2kv.l2kv_decode_attn(Q[layer], Kc[layer], Vc[layer], O[layer], ws)
+        return round(timed(run, 4) * 1e3 / L, 2)
+
+    free, total = torch.cuda.mem_get_info()
+    count = int((free - (10 << 30)) // tensor_bytes)
+    tensors = []
+    for i in range(count):
+        t = torch.empty((L, B, Hkv, n, D), dtype=dt, device=dev)
+        t.view(torch.int16).fill_(1000 + i)
+        tensors.append(t)
+    for _ in range(20):                                                       # clocks up before the first figure
+        decode_us(tensors[0], tensors[1])
+    read = [round(tensor_bytes / timed(lambda t=t: l2kv.l2kv_norms(t, norms), 4) / 1e6) for t in tensors[::2]]
+    apart = args.placement_apart
+    out = {
+        "probe": "placement of the cache in device memory", "device_memory_GiB": round(total / 2**30, 1),
+        "tensors_of_1GiB": count,
+        "norm_pass_read_GBps_every_2nd_tensor": read,
+        "decode_us_per_launch_K_V_neighbours": [decode_us(tensors[i], tensors[i + 1]) for i in range(0, count - 1, 2)],
+        "decode_us_per_launch_K_V_%dGiB_apart" % apart: [decode_us(tensors[i], tensors[i + apart])
+                                                         for i in range(0, count - apart, 2)],
+    }
+    print(json.dumps(out))
+
+
 def main_alr(args, dev):
     """Attention-loss analysis (Sec. 3, Eq. 5-7) at the shape of one layer of the
     chosen workload, repeated over `--layers` layers (default 4): discard ranks
@@ -560,6 +613,11 @@ def main():
     ap.add_argument("--alr", action="store_true",
                     help="time the attention-loss analysis (norm ranks + losses + Y) at the workload's "
                          "per-layer shape instead of the hot path")
+    ap.add_argument("--placement-probe", action="store_true",
+                    help="instead of the benchmark: read rate of the norm pass and time of a decode launch "
+                         "against the position of the cache in device memory (fills the memory)")
+    ap.add_argument("--placement-apart", type=int, default=100,
+                    help="placement probe: distance in GiB between the K and the V tensor of its second decode map")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (torch) before the timed region: "
                          "the known-size kernel that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -575,6 +633,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.placement_probe:
+        return main_placement(args, dev)
     if args.workload in synth.STREAM_CONFIGS:
         return main_stream(args, dev)
     if args.alr:

@@ -256,6 +256,24 @@ def test_decode_all_group_sizes(dev, dt, D, G):
     assert err <= ATTN_GATE and err <= ATTN_BAR, err
 
 
+@pytest.mark.parametrize("dt,D", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128), ("bf16", 256)])
+@pytest.mark.parametrize("G", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_decode_both_final_merges_for_every_build(dev, dt, D, G):
+    # every (element type, head size, query group) build with 2, 8 (final merge in registers),
+    # 9 and 31 workgroups per head (final merge through LDS tables), ragged length
+    if D == 256 and G > 4:
+        pytest.skip("rows of 256 elements: groups of up to 4 query heads")
+    rng = np.random.default_rng(G * 31 + D)
+    B, Hkv, n = 1, 2, 1999
+    Q, K, V = attn_case(rng, B, Hkv * G, Hkv, n, D, dt)
+    want = oracle.decode_attn(Q, K, V, dt)
+    Qd, Kd, Vd = to_dev(Q, dt, dev), to_dev(K, dt, dev), to_dev(V, dt, dev)
+    for s in (2, 8, 9, 31):
+        got = gpu_decode(Qd, Kd, Vd, n_splits=s).cpu().numpy()
+        err = np.abs(got - want).max()
+        assert err <= ATTN_BAR, (s, err)
+
+
 @pytest.mark.parametrize("n", [1, 2, 15, 16, 17, 63, 64, 65, 127, 129, 1000, 4099])
 def test_decode_ragged_lengths_and_split_counts(dev, n):
     rng = np.random.default_rng(n)

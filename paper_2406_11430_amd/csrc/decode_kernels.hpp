@@ -91,26 +91,23 @@ constexpr int kWaitVmcnt0 = 0x0F70;
 #error "the s_waitcnt immediate above is the gfx950 encoding: this file is written for gfx950 only"
 #endif
 
-// Device-scope (agent) relaxed store / load of one float.
+// Device-scope (agent) relaxed store of one float.
 __device__ __forceinline__ void publish(float* p, float v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float fetch(const float* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
-// 16-byte device-scope load: the same cache policy (sc1) the compiler emits for an
-// agent-scope atomic load of one dword, on a four-dword buffer load.  `region` describes
-// the bytes that may be read (the hardware returns zero outside it).
+// Device-scope loads of the published values: buffer loads with the cache policy (sc1) the
+// compiler emits for an agent-scope atomic load of one dword, 16, 8 or 4 bytes wide.  `region`
+// describes the bytes that may be read (the hardware returns zero outside it); offsets are
+// 32-bit, so no 64-bit address arithmetic stands between the ticket and the loads.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
 constexpr int kBufferWord3 = 0x00020000;     // raw buffer, 32-bit data format
 constexpr int kCachePolicySc1 = 16;
 __device__ __forceinline__ f32x4 fetch4(__amdgpu_buffer_rsrc_t region, int byte_offset) {
     return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(region, byte_offset, 0, kCachePolicySc1));
 }
 
-// 8-byte and 4-byte loads with the same policy; voffset per lane, soffset uniform, both in bytes.
+// voffset per lane, soffset uniform, both in bytes
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ f32x2 fetch2(__amdgpu_buffer_rsrc_t region, int voffset, int soffset) {
     return __builtin_bit_cast(f32x2, __builtin_amdgcn_raw_buffer_load_b64(region, voffset, soffset, kCachePolicySc1));

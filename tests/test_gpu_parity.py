@@ -275,6 +275,20 @@ def test_decode_both_final_merges_for_every_build(dev, dt, D, G):
         assert err <= ATTN_BAR, (s, err)
 
 
+@pytest.mark.parametrize("dt,D,G", [("bf16", 128, 8), ("bf16", 128, 4), ("bf16", 128, 1), ("f32", 128, 7),
+                                    ("bf16", 64, 8), ("bf16", 256, 4), ("f32", 64, 3)])
+def test_decode_with_the_maximum_number_of_workgroups_per_head(dev, dt, D, G):
+    # 256 workgroups for one KV head: every table of the final merge at its largest
+    rng = np.random.default_rng(G + D)
+    B, Hkv, n = 1, 1, 16391
+    Q, K, V = attn_case(rng, B, Hkv * G, Hkv, n, D, dt)
+    want = oracle.decode_attn(Q, K, V, dt)
+    smax = l2kv.l2kv_decode_max_splits(n)
+    assert smax == 256
+    got = gpu_decode(to_dev(Q, dt, dev), to_dev(K, dt, dev), to_dev(V, dt, dev), n_splits=smax).cpu().numpy()
+    assert np.abs(got - want).max() <= ATTN_BAR
+
+
 @pytest.mark.parametrize("n", [1, 2, 15, 16, 17, 63, 64, 65, 127, 129, 1000, 4099])
 def test_decode_ragged_lengths_and_split_counts(dev, n):
     rng = np.random.default_rng(n)

@@ -109,6 +109,16 @@ __device__ __forceinline__ f32x4 fetch4(__amdgpu_buffer_rsrc_t region, int byte_
 
 // voffset per lane, soffset uniform, both in bytes
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2p __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4p __attribute__((ext_vector_type(4)));
+// Device-scope stores of 8 and 16 bytes: the policy of publish() on wider stores, so that the
+// lanes of a store instruction write contiguous bytes.
+__device__ __forceinline__ void publish2(__amdgpu_buffer_rsrc_t region, int voffset, f32x2 v) {
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2p, v), region, voffset, 0, kCachePolicySc1);
+}
+__device__ __forceinline__ void publish4(__amdgpu_buffer_rsrc_t region, int voffset, f32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4p, v), region, voffset, 0, kCachePolicySc1);
+}
 __device__ __forceinline__ f32x2 fetch2(__amdgpu_buffer_rsrc_t region, int voffset, int soffset) {
     return __builtin_bit_cast(f32x2, __builtin_amdgcn_raw_buffer_load_b64(region, voffset, soffset, kCachePolicySc1));
 }
@@ -631,12 +641,11 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
             // of the device reads from, so the merging workgroup below sees them
             // without any bulk cache write-back.
             float* out = partial + ((hq0 + g) * n_splits_grid + split) * kRow;
-#pragma unroll
-            for (int k = 0; k < kVec; ++k) publish(out + d + k, num[k]);
-            if (d == 0) {
-                publish(out + D, mx);
-                publish(out + D + 1, den);
-            }
+            const __amdgpu_buffer_rsrc_t row = __builtin_amdgcn_make_buffer_rsrc(out, 0, kRow * (int)sizeof(float), kBufferWord3);
+            if constexpr (kVec == 4) publish4(row, d * (int)sizeof(float), f32x4{num[0], num[1], num[2], num[3]});
+            else if constexpr (kVec == 2) publish2(row, d * (int)sizeof(float), f32x2{num[0], num[1]});
+            else publish(out + d, num[0]);
+            if (d == 0) publish2(row, D * (int)sizeof(float), f32x2{mx, den});
         }
     }
     if (n_splits == 1) {

@@ -46,7 +46,7 @@ HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak (8 TB/s): the figure e
 # plain 1 GiB copy in the same runs): profiles/hot_path_hbm_traffic_pmc.md.
 # A constant from that offline profile, not something this run measures;
 # reported only when the timed shape is that shape.
-PROFILED_DECODE_TRAFFIC_BYTES = {("bf16", 4, 8, 32, 128, 16384): (263059 + 527) * 1024}
+PROFILED_DECODE_TRAFFIC_BYTES = {("bf16", 4, 8, 32, 128, 16384): (263029 + 491) * 1024}
 
 
 def host_threads():

@@ -114,13 +114,75 @@ void norms_kernel(const char* __restrict__ K, int64_t T, int64_t head_stride_byt
     if (c < kNormUnroll && row < T) norms[head * T + row] = mine;
 }
 
+// 128-byte rows (bf16, 64 elements): two consecutive rows are 256 contiguous bytes, so the 16
+// lanes of a row group take a PAIR of rows with one 16-byte load each (lanes 0..7 the even row,
+// lanes 8..15 the odd one) instead of one row with 8-byte loads.  A lane then holds two of the
+// 16 chunks of the fixed summation order (chunk = 4 elements): it sums each left to right, adds
+// the two (first level of the tree), and the remaining three levels run over the 8 lanes of
+// its row.  Bit-identical to the one-row-per-row-group kernel above.
+template <bool kKeep>
+__global__ __launch_bounds__(kNormThreads)
+void norms_row_pairs_kernel(const char* __restrict__ K, int64_t T, int64_t head_stride_bytes,
+                            int64_t blocks_per_head, float* __restrict__ norms) {
+#pragma clang fp contract(off)
+    constexpr int kRowBytes = 128;
+    const int64_t head = blockIdx.x / blocks_per_head;
+    const int64_t chunk = blockIdx.x % blocks_per_head;
+    const int lane = threadIdx.x % kWaveSize;
+    const int wave = threadIdx.x / kWaveSize;
+    const int c = lane % kRowLanes;
+    const int rg = lane / kRowLanes;
+    const int half = c / 8;               // which row of the pair
+    const int j = c % 8;                  // 16-byte piece of that row
+
+    // Row group (wave, rg) owns kNormUnroll consecutive pairs of rows.
+    const int64_t first = chunk * kNormRowsPerBlock + (wave * kRowsPerWaveLoad + rg) * kNormUnroll;   // in pairs
+    const char* head_base = K + head * head_stride_bytes;
+
+    Words<4> raw[kNormUnroll];
+#pragma unroll
+    for (int u = 0; u < kNormUnroll; ++u) {
+        int64_t row = 2 * (first + u) + half;
+        row = row < T ? row : T - 1;      // tail: re-read the last row, result unused
+        const char* p = head_base + row * kRowBytes + j * 16;
+        if constexpr (kKeep) raw[u] = load_words<4>(p);
+        else raw[u] = load_words_stream<4>(p);
+    }
+
+    float mine = 0.f;
+#pragma unroll
+    for (int u = 0; u < kNormUnroll; ++u) {
+        float x[8];
+        widen<BF16, 128>(raw[u], x);      // 4 words -> 8 values in element order
+        float a = x[0] * x[0];
+        float b = x[4] * x[4];
+#pragma unroll
+        for (int e = 1; e < 4; ++e) {
+            float sa = x[e] * x[e];
+            float sb = x[4 + e] * x[4 + e];
+            a = a + sa;
+            b = b + sb;
+        }
+        float v = a + b;                                  // chunks 2j and 2j+1
+        v = v + dpp_read<kDppXor1>(v);
+        v = v + dpp_read<kDppXor2>(v);
+        v = v + dpp_read<kDppHalfMirror>(v);              // the 8 lanes of this row
+        mine = (j == u) ? v : mine;       // lane j of each half keeps the sum of pair u's row
+    }
+    const int64_t row = 2 * (first + j) + half;
+    if (j < kNormUnroll && row < T) norms[head * T + row] = mine;
+}
+
 template <typename E, int D>
 static l2kv_status launch_norms(const void* K, int64_t n_heads, int64_t T, int64_t head_stride,
                                 float* norms, bool keep_in_cache, hipStream_t stream) {
-    const int64_t bph = (T + kNormRowsPerBlock - 1) / kNormRowsPerBlock;
+    constexpr bool kPairs = Slice<E, D>::kRowBytes == 128;                    // a block takes twice the rows then
+    const int64_t rows_per_block = kNormRowsPerBlock * (kPairs ? 2 : 1);
+    const int64_t bph = (T + rows_per_block - 1) / rows_per_block;
     const int64_t blocks = bph * n_heads;
     if (blocks > 0x7fffffffLL) return L2KV_ERR_SHAPE;
     auto kernel = keep_in_cache ? norms_kernel<E, D, true> : norms_kernel<E, D, false>;
+    if constexpr (kPairs) kernel = keep_in_cache ? norms_row_pairs_kernel<true> : norms_row_pairs_kernel<false>;
     hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNormThreads), 0, stream,
                        static_cast<const char*>(K), T, head_stride * (int64_t)E::kBytes, bph, norms);
     return launch_status();

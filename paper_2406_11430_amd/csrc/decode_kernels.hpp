@@ -65,9 +65,9 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
 
 // Row element held in fp32 slot e of the slice of lane c (slots in the order of widen()), with
 // the row shared among the lanes in 16-byte pieces (Pieces in l2kv_device.hpp).
-template <typename E, int D>
+template <typename E, int W>
 __device__ __forceinline__ constexpr int slice_elem(int c, int e) {
-    using P = Pieces<Slice<E, D>::kWords>;
+    using P = Pieces<W>;
     constexpr int per_piece = P::kBytes / E::kBytes;
     return (e / per_piece) * (P::kStride / E::kBytes) + c * per_piece + e % per_piece;
 }
@@ -152,25 +152,67 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 // the 16 lanes that read the same 16-byte column of 16 different rows hit different banks.
 constexpr int kKtRow = 272;
 
-template <typename E, int D>
-struct Tile {
-    Words<Slice<E, D>::kWords> k[kDecLoads];
-    Words<Slice<E, D>::kWords> v[kDecLoads];
+// How the 16 lanes of a row group share the rows in these kernels.  Rows of 256 and 512 bytes:
+// one row per 16 lanes.  Rows of 128 bytes (bf16, 64 elements): two consecutive rows are 256
+// contiguous bytes, so a row group takes a PAIR of rows with one 16-byte load per lane (lanes
+// 0..7 the even row, 8..15 the odd one) -- the same load instructions as for 256-byte rows
+// instead of 8-byte loads -- and runs one online softmax per 8 lanes.
+template <typename E, int D> struct DecodeGeometry {
+    using S = Slice<E, D>;
+    static constexpr int kRowsPerSlot = S::kRowBytes == 128 ? 2 : 1;        // rows per 16 lanes and load
+    static constexpr int kLanesPerRow = kRowLanes / kRowsPerSlot;
+    static constexpr int kWords = S::kWords * kRowsPerSlot;                  // 32-bit words per lane
+    static constexpr int kElems = S::kElems * kRowsPerSlot;                  // row elements per lane
+    static constexpr int kSlotBytes = S::kRowBytes * kRowsPerSlot;           // bytes per 16 lanes and load
+    static constexpr int kTileRows = kDecRowsPerStep * kRowsPerSlot;         // rows per wave step
+    static constexpr int kGroups = kDecGroups * kRowsPerSlot;                // softmax streams per workgroup
 };
 
-// Loads the 16 rows [first_row, first_row+16) of K and V for this lane; all 16
-// rows must exist.  lane_off = rg * row_bytes + c * piece_bytes.
+// Sum over the lanes that share a row: 16, or 8 for row pairs (same tree, one level less).
+template <int kLanes>
+__device__ __forceinline__ float row_tree_sum(float p) {
+    p = p + dpp_read<kDppXor1>(p);
+    p = p + dpp_read<kDppXor2>(p);
+    p = p + dpp_read<kDppHalfMirror>(p);
+    if constexpr (kLanes == 16) p = p + dpp_read<kDppMirror>(p);
+    return p;
+}
+
+// A lane's words as fp32 values in element order.
+template <typename E, int W>
+__device__ __forceinline__ void widen_words(const Words<W>& r, float (&x)[W * 4 / E::kBytes]) {
+    if constexpr (E::kBytes == 4) {
+#pragma unroll
+        for (int i = 0; i < W; ++i) x[i] = __builtin_bit_cast(float, r.w[i]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < W; ++i) {
+            x[2 * i] = bf16_lo(r.w[i]);
+            x[2 * i + 1] = bf16_hi(r.w[i]);
+        }
+    }
+}
+
+template <typename E, int D>
+struct Tile {
+    Words<DecodeGeometry<E, D>::kWords> k[kDecLoads];
+    Words<DecodeGeometry<E, D>::kWords> v[kDecLoads];
+};
+
+// Loads the tile of rows that starts at first_row (16 rows, 32 for row pairs) of K and V for
+// this lane; all its rows must exist.  lane_off = rg * slot_bytes + c * piece_bytes.
 template <typename E, int D>
 __device__ __forceinline__ void load_tile(Tile<E, D>& t, const char* Kh, const char* Vh,
                                           int64_t first_row, int lane_off) {
     using S = Slice<E, D>;
+    using Geo = DecodeGeometry<E, D>;
     const int64_t off = first_row * S::kRowBytes + lane_off;
 #pragma unroll
     for (int u = 0; u < kDecLoads; ++u)
-        t.k[u] = stream_words<S::kWords>(Kh + off + u * (kRowsPerWaveLoad * S::kRowBytes));
+        t.k[u] = stream_words<Geo::kWords>(Kh + off + u * (kRowsPerWaveLoad * Geo::kSlotBytes));
 #pragma unroll
     for (int u = 0; u < kDecLoads; ++u)
-        t.v[u] = stream_words<S::kWords>(Vh + off + u * (kRowsPerWaveLoad * S::kRowBytes));
+        t.v[u] = stream_words<Geo::kWords>(Vh + off + u * (kRowsPerWaveLoad * Geo::kSlotBytes));
 }
 
 // Ragged last tile of a row range: rows past last_valid re-read row last_valid
@@ -179,17 +221,18 @@ template <typename E, int D>
 __device__ __forceinline__ void load_tile_clamped(Tile<E, D>& t, const char* Kh, const char* Vh,
                                                   int64_t first_row, int64_t last_valid, int rg, int c) {
     using S = Slice<E, D>;
+    using Geo = DecodeGeometry<E, D>;
     int64_t off[kDecLoads];
 #pragma unroll
     for (int u = 0; u < kDecLoads; ++u) {
-        int64_t row = first_row + u * kRowsPerWaveLoad + rg;
+        int64_t row = first_row + (u * kRowsPerWaveLoad + rg) * Geo::kRowsPerSlot + c / Geo::kLanesPerRow;
         row = row < last_valid ? row : last_valid;
-        off[u] = row * S::kRowBytes + c * Pieces<S::kWords>::kBytes;
+        off[u] = row * S::kRowBytes + (c % Geo::kLanesPerRow) * Pieces<Geo::kWords>::kBytes;
     }
 #pragma unroll
-    for (int u = 0; u < kDecLoads; ++u) t.k[u] = stream_words<S::kWords>(Kh + off[u]);
+    for (int u = 0; u < kDecLoads; ++u) t.k[u] = stream_words<Geo::kWords>(Kh + off[u]);
 #pragma unroll
-    for (int u = 0; u < kDecLoads; ++u) t.v[u] = stream_words<S::kWords>(Vh + off[u]);
+    for (int u = 0; u < kDecLoads; ++u) t.v[u] = stream_words<Geo::kWords>(Vh + off[u]);
 }
 
 // The builds that use the matrix unit (bf16, D = 128, 6 to 8 query heads per KV head) state an
@@ -220,8 +263,11 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
                                             float* __restrict__ partial, float* __restrict__ O, int out_bf16,
                                             uint32_t* __restrict__ queue, uint32_t& drawn) {
     using S = Slice<E, D>;
-    constexpr int EPL = S::kElems;
-    constexpr int W = S::kWords;
+    using Geo = DecodeGeometry<E, D>;
+    constexpr int EPL = Geo::kElems;
+    constexpr int W = Geo::kWords;
+    constexpr int kLanesPerRow = Geo::kLanesPerRow;
+    constexpr int kGroups = Geo::kGroups;
     constexpr bool kBf16 = E::kBytes == 2;
     constexpr float kNegInf = -INFINITY;
     constexpr int kRow = D + 4;                      // floats per partial row (decode_partial_floats)
@@ -231,16 +277,16 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
     constexpr int kQuads = G * D / 4;                                   // float4 pieces of the G output rows
     constexpr int kWays = kDecThreads / kQuads;                         // threads sharing one piece, >= 1
     static_assert(kQuads <= kDecThreads, "more output pieces than threads");
-    constexpr int kAccFloats = kDecGroups * G * D;
+    constexpr int kAccFloats = kGroups * G * D;
     constexpr int kTabFloats = 3 * G * kDecodeMaxSplits + kWays * G * D;
-    constexpr int kLdsFloats = kAccFloats + 2 * kDecGroups * G > kTabFloats ? kAccFloats + 2 * kDecGroups * G : kTabFloats;
+    constexpr int kLdsFloats = kAccFloats + 2 * kGroups * G > kTabFloats ? kAccFloats + 2 * kGroups * G : kTabFloats;
     __shared__ __attribute__((aligned(16))) float s_raw[kLdsFloats];
     __shared__ uint32_t s_ticket;
     __shared__ float s_max[G];                   // per query head: maximum of the workgroups' m (final merge)
     if (threadIdx.x < G) s_max[threadIdx.x] = -INFINITY;       // ordered before its use by the barriers below
     float* const s_acc = s_raw;                                          // [(grp * G + g) * D + d]
     float* const s_m = s_raw + kAccFloats;                               // [grp * G + g]
-    float* const s_l = s_m + kDecGroups * G;
+    float* const s_l = s_m + kGroups * G;
 
     const int lane = threadIdx.x % kWaveSize;
     // the wave index is the same in all 64 lanes: keep it in a scalar register
@@ -255,14 +301,14 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
     float qf[kBf16 ? 1 : G][kBf16 ? 1 : EPL];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        Words<W> raw = cached_words<W>(Q + (hq0 + g) * S::kRowBytes + c * Pieces<W>::kBytes);
+        Words<W> raw = cached_words<W>(Q + (hq0 + g) * S::kRowBytes + (c % kLanesPerRow) * Pieces<W>::kBytes);
 #pragma unroll
         for (int w = 0; w < W; ++w) qw[g][w] = raw.w[w];
-        if constexpr (!kBf16) widen<E, D>(raw, qf[g]);
+        if constexpr (!kBf16) widen_words<E, W>(raw, qf[g]);
     }
 
     const int64_t r1 = kv_len;                   // rows at or past r1 do not exist
-    const int lane_off = rg * S::kRowBytes + c * Pieces<W>::kBytes;
+    const int lane_off = rg * Geo::kSlotBytes + c * Pieces<W>::kBytes;
 
     float m[G], l[G], acc[G][EPL];    // m: running max of the RAW score (before scaling)
 #pragma unroll
@@ -388,7 +434,7 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
 #pragma unroll
                 for (int u = 0; u < kDecLoads; ++u) {
                     float vx[EPL];
-                    widen<E, D>(t.v[u], vx);
+                    widen_words<E, W>(t.v[u], vx);
 #pragma unroll
                     for (int e = 0; e < EPL; ++e) {
                         accq0[e] = __builtin_amdgcn_mfma_f32_4x4x1f32(pa[u], vx[e], accq0[e], 0, 0, 0);
@@ -409,7 +455,7 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
 #pragma unroll
                 for (int u = 0; u < kDecLoads; ++u) {
                     float vx[EPL];
-                    widen<E, D>(t.v[u], vx);
+                    widen_words<E, W>(t.v[u], vx);
 #pragma unroll
                     for (int g = 0; g < G; ++g)
 #pragma unroll
@@ -434,7 +480,7 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
                 }
             } else {
                 float kx[EPL];
-                widen<E, D>(t.k[u], kx);
+                widen_words<E, W>(t.k[u], kx);
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
                     float a = qf[g][0] * kx[0];
@@ -447,11 +493,11 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int u = 0; u < kDecLoads; ++u) s[g][u] = row16_tree_sum(s[g][u]);
+            for (int u = 0; u < kDecLoads; ++u) s[g][u] = row_tree_sum<kLanesPerRow>(s[g][u]);
         if (ragged) {                                    // only the last, partial tile of a range
 #pragma unroll
             for (int u = 0; u < kDecLoads; ++u) {
-                const bool valid = first_row + u * kRowsPerWaveLoad + rg < r1;
+                const bool valid = first_row + (u * kRowsPerWaveLoad + rg) * Geo::kRowsPerSlot + c / kLanesPerRow < r1;
 #pragma unroll
                 for (int g = 0; g < G; ++g) s[g][u] = valid ? s[g][u] : kNegInf;
             }
@@ -479,7 +525,7 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
 #pragma unroll
         for (int u = 0; u < kDecLoads; ++u) {
             float vx[EPL];
-            widen<E, D>(t.v[u], vx);
+            widen_words<E, W>(t.v[u], vx);
 #pragma unroll
             for (int g = 0; g < G; ++g)
 #pragma unroll
@@ -505,12 +551,12 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
     // (if any) is handled by its owner afterwards with clamped loads and
     // masked scores.
     {
-        const int64_t n_full = kv_len / kDecRowsPerStep;                       // full tiles in the head
+        const int64_t n_full = kv_len / Geo::kTileRows;                         // full tiles in the head
         const int64_t first_tile = (int64_t)split * kDecWaves + wave;
         const int64_t tile_stride = (int64_t)n_splits * kDecWaves;
         const int64_t mine = n_full > first_tile ? (n_full - first_tile + tile_stride - 1) / tile_stride : 0;
-        const int64_t kStride = tile_stride * kDecRowsPerStep;                 // rows between my tiles
-        int64_t row = first_tile * kDecRowsPerStep;
+        const int64_t kStride = tile_stride * Geo::kTileRows;                  // rows between my tiles
+        int64_t row = first_tile * Geo::kTileRows;
         if (mine > 0) {
             Tile<E, D> ta, tb;
             // The scheduling barriers pin each batch of loads ahead of the
@@ -540,10 +586,10 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
                 consume(ta, row, false);
             }
         }
-        if (kv_len % kDecRowsPerStep != 0 && (n_full / kDecWaves) % n_splits == split &&
+        if (kv_len % Geo::kTileRows != 0 && (n_full / kDecWaves) % n_splits == split &&
             n_full % kDecWaves == wave) {
             Tile<E, D> tt;
-            const int64_t first = n_full * kDecRowsPerStep;
+            const int64_t first = n_full * Geo::kTileRows;
             load_tile_clamped<E, D>(tt, Kh, Vh, first, r1 - 1, rg, c);
             consume(tt, first, true);
         }
@@ -581,12 +627,13 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
 
     // ---- merge the 16 row groups of the workgroup through LDS --------------
     if constexpr (kMfma) __syncthreads();          // every wave is done with its buffers in that array
-    const int grp = wave * kRowsPerWaveLoad + rg;
+    const int grp = (wave * kRowsPerWaveLoad + rg) * Geo::kRowsPerSlot + c / kLanesPerRow;
+    const int cr = c % kLanesPerRow;               // position among the lanes of this row
 #pragma unroll
     for (int g = 0; g < G; ++g) {
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) s_acc[(grp * G + g) * D + slice_elem<E, D>(c, e)] = acc[g][e];
-        if (c == 0) {
+        for (int e = 0; e < EPL; ++e) s_acc[(grp * G + g) * D + slice_elem<E, W>(cr, e)] = acc[g][e];
+        if (cr == 0) {
             s_m[grp * G + g] = m[g] * scale_log2e;     // -inf stays -inf (scale > 0)
             s_l[grp * G + g] = l[g];
         }
@@ -601,9 +648,9 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
     if (o0 < G * D) {
         const int g = o0 / D;
         const int d = o0 % D;
-        float mi[kDecGroups], li[kDecGroups], ai[kDecGroups][kVec];
+        float mi[kGroups], li[kGroups], ai[kGroups][kVec];
 #pragma unroll
-        for (int i = 0; i < kDecGroups; ++i) {
+        for (int i = 0; i < kGroups; ++i) {
             mi[i] = s_m[i * G + g];
             li[i] = s_l[i * G + g];
             const float* a = s_acc + (i * G + g) * D + d;
@@ -620,12 +667,12 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
         __builtin_amdgcn_sched_barrier(0);
         float mx = kNegInf;
 #pragma unroll
-        for (int i = 0; i < kDecGroups; ++i) mx = fmaxf(mx, mi[i]);
+        for (int i = 0; i < kGroups; ++i) mx = fmaxf(mx, mi[i]);
         float num[kVec], den = 0.f;
 #pragma unroll
         for (int k = 0; k < kVec; ++k) num[k] = 0.f;
 #pragma unroll
-        for (int i = 0; i < kDecGroups; ++i) {
+        for (int i = 0; i < kGroups; ++i) {
             const float w = mi[i] == kNegInf ? 0.f : fast_exp2(mi[i] - mx);
 #pragma unroll
             for (int k = 0; k < kVec; ++k) num[k] = fmaf(w, ai[i][k], num[k]);

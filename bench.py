@@ -241,6 +241,12 @@ class StreamWorkload:
         self.in_off, self.out_off, self.slot_off = off(lens), off(self.k0), off(caps)
         self.total, self.total_kept, self.total_slots = sum(lens), sum(self.k0), sum(caps)
         self.max_len, self.max_kept, self.max_cap = max(lens), max(self.k0), max(caps)
+        # The slot cache is the long-lived object: allocated first, its K and V halves in one
+        # allocation.  (Where tensors lie in device memory matters on this GPU: a launch whose K and
+        # V streams come from different thirds of the memory runs about 9 % slower,
+        # profiles/placement_in_device_memory.md.)
+        self.KVc = torch.zeros((2, P, self.total_slots, D), dtype=dt, device=dev)
+        self.Kc, self.Vc = self.KVc[0], self.KVc[1]
         self.K = torch.empty((P, self.total, D), dtype=dt, device=dev)
         self.V = torch.empty_like(self.K)
         for layer in range(L):
@@ -256,8 +262,6 @@ class StreamWorkload:
             self.Knew[t].copy_(a), self.Vnew[t].copy_(b), self.Q[t].copy_(q)
         self.norms = torch.empty((P, self.total), dtype=torch.float32, device=dev)
         self.idx = torch.empty((P, self.total_kept), dtype=torch.int32, device=dev)
-        self.Kc = torch.zeros((P, self.total_slots, D), dtype=dt, device=dev)
-        self.Vc = torch.zeros_like(self.Kc)
         self.nc = torch.zeros((P, self.total_slots), dtype=torch.float32, device=dev)
         self.pc = torch.zeros((P, self.total_slots), dtype=torch.int32, device=dev)
         self.lens_init = torch.tensor(self.k0, dtype=torch.int32, device=dev)

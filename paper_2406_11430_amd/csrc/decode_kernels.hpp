@@ -6,14 +6,15 @@
 //
 // Decomposition: grid (split, sequence x KV head).  The n_splits workgroups of a
 // KV head take turns on consecutive 64-row blocks of its cache and stream them
-// once for all G = Hq/Hkv query heads.  16 lanes share a row (16 bytes each),
-// a wave covers 16 rows of K and of V per step (4 + 4 non-temporal loads per
-// lane) and always has its next tile in flight while it computes on the
-// current one (two register tiles, ping-pong, no branch between a load and its
-// use so the wait counters stay exact).  Every 16-lane row group runs its own
-// online softmax (running max m, denominator l, weighted value sum acc), so the
-// only cross-lane traffic in the loop is the 4-step DPP tree of each dot
-// product.
+// once for all G = Hq/Hkv query heads.  16 lanes share a row (16 bytes per lane
+// and load: one piece of a 256-byte row, two pieces of a 512-byte row; rows of
+// 128 bytes are taken in pairs, 8 lanes each -- DecodeGeometry), a wave covers
+// 16 rows of K and of V per step (4 + 4 non-temporal loads per lane) and always
+// has its next tile in flight while it computes on the current one (two
+// register tiles, ping-pong, no branch between a load and its use so the wait
+// counters stay exact).  Every row group runs its own online softmax (running
+// max m, denominator l, weighted value sum acc), so the only cross-lane traffic
+// in the loop is the DPP tree of each dot product.
 //
 // bf16 caches: q.k uses the packed bf16 dot instruction with fp32 accumulate
 // (both operands are exact bf16 inputs); the softmax scale is applied to the
@@ -23,14 +24,17 @@
 // instead, run the softmax once per (head, row) and, in grid launches, form p.V
 // on the matrix unit in fp32; see decode_item.
 //
-// At the end the 16 row groups of the workgroup are merged through LDS.  A KV
+// At the end the row groups of the workgroup are merged through LDS.  A KV
 // head with a single workgroup writes O from that merge.  Otherwise one partial
 // (acc[D], m, l) per query head goes to the workspace, and the workgroup that
 // finishes last for its KV head (device-scope counter in the workspace) merges
 // the partials of all workgroups and writes O: one kernel per call.  Two builds
 // of that final merge (template parameter kWideMerge): for at most 8 workgroups
 // per head everything stays in registers; for more, the weights are formed once
-// in LDS and the accumulators arrive as 16-byte device-scope loads.
+// in LDS and the accumulators arrive as 16-byte device-scope loads.  In both
+// merges a thread forms 1, 2 or 4 consecutive output elements of one head and
+// issues all its reads before the first use: every step of this epilogue is a
+// memory or LDS round trip on the critical path of the launch.
 //
 // The same routine (decode_item) runs under two launch shapes: a grid
 // (decode_kernel) and, for ragged batches with a known longest-first order, a

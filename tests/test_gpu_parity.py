@@ -762,3 +762,33 @@ def test_random_shapes_whole_path(dev):
         for ns in {0, 1, int(rng.integers(1, smax + 1)), smax}:
             got = gpu_decode(to_dev(Q, dt, dev), Kcd, Vcd, n_splits=ns).cpu().numpy()
             assert np.abs(got - want).max() <= ATTN_BAR, (case, dt, D, B, Hkv, G, T, k, ns)
+
+
+def test_random_shapes_rows_of_128_and_512_bytes(dev):
+    # the same sweep on the row sizes that do not take one 16-byte load per lane and row: pairs of
+    # 128-byte rows (bf16, 64 elements) and 512-byte rows in two pieces (bf16 256, fp32 128)
+    rng = np.random.default_rng(1130)
+    for case in range(30):
+        dt, D = (("bf16", 64), ("bf16", 256), ("f32", 128))[case % 3]
+        B, Hkv = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        G = int(rng.integers(1, 5 if D == 256 else 9))
+        T = int(rng.integers(1, 3000))
+        r = float(rng.uniform(0.02, 1.0))
+        k = oracle.keep_count(T, r)
+        K, V = rand_cache(rng, (B, Hkv, T, D), dt), rand_cache(rng, (B, Hkv, T, D), dt)
+        Q = rand_cache(rng, (B, Hkv * G, D), dt)
+        n32, _, idx, Kc, Vc = oracle.compress(K, V, dt, r)
+        Kd, Vd = to_dev(K, dt, dev), to_dev(V, dt, dev)
+        nd = gpu_norms(Kd)
+        assert np.array_equal(nd.cpu().numpy().view(np.uint32), n32.view(np.uint32)), case
+        idd, _ = gpu_select(nd, k)
+        assert np.array_equal(idd.cpu().numpy(), idx), (case, T, k)
+        Kcd = torch.empty((B, Hkv, k, D), dtype=Kd.dtype, device=dev)
+        Vcd = torch.empty_like(Kcd)
+        l2kv.l2kv_compact(Kd, Vd, idd, Kcd, Vcd)
+        assert np.array_equal(synth.as_numpy_bits(Kcd), Kc) and np.array_equal(synth.as_numpy_bits(Vcd), Vc), case
+        want = oracle.decode_attn(Q, Kc, Vc, dt)
+        smax = l2kv.l2kv_decode_max_splits(k)
+        for ns in {0, 1, int(rng.integers(1, smax + 1)), smax}:
+            got = gpu_decode(to_dev(Q, dt, dev), Kcd, Vcd, n_splits=ns).cpu().numpy()
+            assert np.abs(got - want).max() <= ATTN_BAR, (case, dt, D, B, Hkv, G, T, k, ns)

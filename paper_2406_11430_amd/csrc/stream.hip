@@ -246,30 +246,42 @@ void stream_evict_kernel(int64_t n_seq, const int64_t* __restrict__ slot_off, in
     int32_t* pw = pos_c + base;
 
     while (len > budget) {                         // uniform over the workgroup
-        unsigned long long best = 0;
-        int32_t best_slot = -1;
-        // four slots per lane and step, their eight loads issued before the first compare
-        // (positions past the end re-read the last slot, which cannot beat itself)
-        constexpr int kScan = 4;
+        // Per-lane scan over the NORMS only (half of the bytes a scan of norms and token ids would
+        // read): eight slots per lane and step, their loads issued before the first compare
+        // (positions past the end re-read the last slot, which cannot beat itself).  Token ids
+        // are fetched only where they decide: when two norms tie, and once per lane at the end.
+        uint32_t best_norm = 0;
+        int32_t best_slot = -1, best_id = 0;
+        bool have_id = false;
+        constexpr int kScan = 8;
         for (int32_t j0 = threadIdx.x; j0 < len; j0 += kScan * kEvictThreads) {
             uint32_t nv[kScan];
-            int32_t pv[kScan], js[kScan];
+            int32_t js[kScan];
 #pragma unroll
             for (int u = 0; u < kScan; ++u) {
                 const int32_t j = j0 + u * kEvictThreads;
                 js[u] = j < len ? j : len - 1;
                 nv[u] = nb[js[u]];
-                pv[u] = pw[js[u]];
             }
 #pragma unroll
             for (int u = 0; u < kScan; ++u) {
-                const unsigned long long key = ((unsigned long long)nv[u] << 32) | (uint32_t)pv[u];
-                if (best_slot < 0 || key > best) {
-                    best = key;
+                if (best_slot < 0 || nv[u] > best_norm) {
+                    best_norm = nv[u];
                     best_slot = js[u];
+                    have_id = false;
+                } else if (nv[u] == best_norm && js[u] != best_slot) {        // rare: equal norms
+                    if (!have_id) best_id = pw[best_slot];
+                    have_id = true;
+                    const int32_t id = pw[js[u]];
+                    if ((uint32_t)id > (uint32_t)best_id) {
+                        best_id = id;
+                        best_slot = js[u];
+                    }
                 }
             }
         }
+        if (best_slot >= 0 && !have_id) best_id = pw[best_slot];
+        unsigned long long best = ((unsigned long long)best_norm << 32) | (uint32_t)best_id;
         // keys are distinct (token ids are), so "larger key" is a total order; -1 marks "none"
 #pragma unroll
         for (int off = kWaveSize / 2; off > 0; off >>= 1) {

@@ -215,13 +215,16 @@ l2kv_status stream_append_dispatch(const void* Knew, const void* Vnew, l2kv_dtyp
 constexpr int kEvictThreads = 256;
 constexpr int kEvictWaves = kEvictThreads / kWaveSize;
 
-// One workgroup per (plane, sequence).  Every eviction is one arg-max over the
-// occupied slots of key = (norm bits << 32 | token id): per-lane scan, wave
-// reduction with shuffles, 4 wave results through LDS.  In the steady state of
-// a growing budget at most one slot goes per step.
-template <int W>
+// One team of lanes per (plane, sequence): a whole workgroup (kTeam = 256), or one wave of a
+// workgroup that serves four of them (kTeam = 64, for batches whose sequences are short: the
+// work of a team is a chain of dependent loads, so more and smaller teams keep more of them in
+// flight; no LDS and no barrier then).  Every eviction is one arg-max over the occupied slots
+// of key = (norm bits << 32 | token id): per-lane scan, wave reduction with shuffles, and for
+// workgroup teams 4 wave results through LDS.  In the steady state of a growing budget at most
+// one slot goes per step.
+template <int W, int kTeam>
 __global__ __launch_bounds__(kEvictThreads)
-void stream_evict_kernel(int64_t n_seq, const int64_t* __restrict__ slot_off, int64_t total_slots,
+void stream_evict_kernel(int64_t n_seq, int64_t n_teams, const int64_t* __restrict__ slot_off, int64_t total_slots,
                          const int32_t* __restrict__ lens_in, const int32_t* __restrict__ budgets,
                          int32_t* __restrict__ lens_out, char* __restrict__ Kc, char* __restrict__ Vc,
                          float* __restrict__ norms_c, int32_t* __restrict__ pos_c) {
@@ -229,10 +232,13 @@ void stream_evict_kernel(int64_t n_seq, const int64_t* __restrict__ slot_off, in
     constexpr int64_t kRowBytes = kRowLanes * kSliceBytes;
     __shared__ unsigned long long s_key[kEvictWaves];
     __shared__ int32_t s_slot[kEvictWaves];
-    const int64_t seq = blockIdx.x % n_seq;
-    const int64_t plane = blockIdx.x / n_seq;
+    const int64_t team = (int64_t)blockIdx.x * (kEvictThreads / kTeam) + threadIdx.x / kTeam;
+    if (team >= n_teams) return;                   // a whole wave (teams are waves or workgroups)
+    const int tid = threadIdx.x % kTeam;           // position in the team
+    const int64_t seq = team % n_seq;
+    const int64_t plane = team / n_seq;
     const int lane = threadIdx.x % kWaveSize;
-    const int wave = threadIdx.x / kWaveSize;
+    [[maybe_unused]] const int wave = threadIdx.x / kWaveSize;
 
     const Range slots = clamped_range(slot_off, seq, total_slots);
     const int64_t cap = slots.count;
@@ -254,12 +260,12 @@ void stream_evict_kernel(int64_t n_seq, const int64_t* __restrict__ slot_off, in
         int32_t best_slot = -1, best_id = 0;
         bool have_id = false;
         constexpr int kScan = 8;
-        for (int32_t j0 = threadIdx.x; j0 < len; j0 += kScan * kEvictThreads) {
+        for (int32_t j0 = tid; j0 < len; j0 += kScan * kTeam) {
             uint32_t nv[kScan];
             int32_t js[kScan];
 #pragma unroll
             for (int u = 0; u < kScan; ++u) {
-                const int32_t j = j0 + u * kEvictThreads;
+                const int32_t j = j0 + u * kTeam;
                 js[u] = j < len ? j : len - 1;
                 nv[u] = nb[js[u]];
             }
@@ -292,37 +298,41 @@ void stream_evict_kernel(int64_t n_seq, const int64_t* __restrict__ slot_off, in
                 best_slot = os;
             }
         }
-        if (lane == 0) {
-            s_key[wave] = best;
-            s_slot[wave] = best_slot;
-        }
-        __syncthreads();
-        best = s_key[0];
-        best_slot = s_slot[0];
+        if constexpr (kTeam == kEvictThreads) {
+            if (lane == 0) {
+                s_key[wave] = best;
+                s_slot[wave] = best_slot;
+            }
+            __syncthreads();
+            best = s_key[0];
+            best_slot = s_slot[0];
 #pragma unroll
-        for (int w = 1; w < kEvictWaves; ++w) {
-            if (s_slot[w] >= 0 && (best_slot < 0 || s_key[w] > best)) {
-                best = s_key[w];
-                best_slot = s_slot[w];
+            for (int w = 1; w < kEvictWaves; ++w) {
+                if (s_slot[w] >= 0 && (best_slot < 0 || s_key[w] > best)) {
+                    best = s_key[w];
+                    best_slot = s_slot[w];
+                }
             }
         }
         const int32_t last = len - 1;
         if (best_slot != last) {
             // move the last slot into the hole: first 16 lanes K, next 16 lanes V
-            if (threadIdx.x < 2 * kRowLanes) {
-                char* buf = threadIdx.x < kRowLanes ? Kc : Vc;
-                const int c = threadIdx.x % kRowLanes;
+            if (tid < 2 * kRowLanes) {
+                char* buf = tid < kRowLanes ? Kc : Vc;
+                const int c = tid % kRowLanes;
                 const Words<W> row = load_words<W>(buf + (base + last) * kRowBytes + c * kSliceBytes);
                 store_words<W>(buf + (base + best_slot) * kRowBytes + c * kSliceBytes, row);
-            } else if (threadIdx.x == 2 * kRowLanes) {
+            } else if (tid == 2 * kRowLanes) {
                 nw[best_slot] = nw[last];
                 pw[best_slot] = pw[last];
             }
         }
         len = last;
-        __syncthreads();                            // moves visible before the next scan; LDS reusable
+        // moves visible to the team before its next scan (and the LDS reusable)
+        if constexpr (kTeam == kEvictThreads) __syncthreads();
+        else __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
     }
-    if (plane == 0 && threadIdx.x == 0) lens_out[seq] = len;
+    if (plane == 0 && tid == 0) lens_out[seq] = len;
 }
 
 l2kv_status stream_evict_dispatch(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, int32_t D,
@@ -330,11 +340,15 @@ l2kv_status stream_evict_dispatch(l2kv_dtype dt, int32_t n_planes, int32_t n_seq
                                   const int32_t* budgets, int32_t* lens_out, void* Kc, void* Vc,
                                   float* norms_c, int32_t* pos_c, hipStream_t stream) {
     const int row_bytes = D * (dt == L2KV_F32 ? 4 : 2);
-    const int64_t blocks = (int64_t)n_planes * n_seq;
+    const int64_t teams = (int64_t)n_planes * n_seq;
+    // sequences of a few thousand slots on average: one wave per (plane, sequence)
+    const bool waves = total_slots / n_seq <= 8192;
+    const int64_t blocks = waves ? (teams + kEvictWaves - 1) / kEvictWaves : teams;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return L2KV_ERR_SHAPE;
 #define L2KV_EV(WW)                                                                               \
-    hipLaunchKernelGGL((stream_evict_kernel<WW>), dim3((unsigned)blocks), dim3(kEvictThreads), 0,  \
-                       stream, (int64_t)n_seq, slot_off, total_slots, lens_in, budgets, lens_out,  \
+    hipLaunchKernelGGL((waves ? stream_evict_kernel<WW, kWaveSize> : stream_evict_kernel<WW, kEvictThreads>), \
+                       dim3((unsigned)blocks), dim3(kEvictThreads), 0,                            \
+                       stream, (int64_t)n_seq, teams, slot_off, total_slots, lens_in, budgets, lens_out,  \
                        static_cast<char*>(Kc), static_cast<char*>(Vc), norms_c, pos_c)
     switch (row_bytes) {
         case 128: L2KV_EV(2); break;

@@ -106,6 +106,30 @@ __device__ __forceinline__ Words<W> load_words_stream(const void* p) {
     return r;
 }
 
+// The same loads through a buffer descriptor (raw buffer, 32-bit data format): `byte_offset` is
+// a 32-bit per-lane offset from the descriptor's base, bytes outside its range read as zero.
+// Policy: plain, or the non-temporal hint of the streaming loads above.
+constexpr int kRawBufferWord3 = 0x00020000;
+constexpr int kBufferPolicyPlain = 0;
+constexpr int kBufferPolicyStream = 2;
+template <int W, int kPieceStride, int kPolicy>
+__device__ __forceinline__ Words<W> buffer_load_words(__amdgpu_buffer_rsrc_t rsrc, int byte_offset) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    Words<W> r;
+    if constexpr (W == 2) {
+        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, byte_offset, 0, kPolicy);
+        r.w[0] = v.x; r.w[1] = v.y;
+    } else {
+#pragma unroll
+        for (int i = 0; i < W / 4; ++i) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_offset + i * kPieceStride, 0, kPolicy);
+            r.w[4 * i + 0] = v.x; r.w[4 * i + 1] = v.y; r.w[4 * i + 2] = v.z; r.w[4 * i + 3] = v.w;
+        }
+    }
+    return r;
+}
+
 template <int W, int kPieceStride = 16>
 __device__ __forceinline__ void store_words_stream(void* p, const Words<W>& r) {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));

@@ -41,26 +41,33 @@ void norms_kernel(const char* __restrict__ K, int64_t T, int64_t head_stride_byt
     using S = Slice<E, D>;
     using P = Pieces<S::kWords>;
     static_assert(P::kCount <= 2, "rows of at most 512 bytes");
-    const int64_t head = blockIdx.x / blocks_per_head;
-    const int64_t chunk = blockIdx.x % blocks_per_head;
+    // grid (chunks, heads) when the head count fits the y dimension; else one long x dimension
+    // cut by a 32-bit division (the launcher checked that the block count fits 31 bits)
+    const int64_t head = blocks_per_head == 0 ? blockIdx.y : blockIdx.x / (uint32_t)blocks_per_head;
+    const int64_t chunk = blocks_per_head == 0 ? blockIdx.x : blockIdx.x % (uint32_t)blocks_per_head;
     const int lane = threadIdx.x % kWaveSize;
     const int wave = threadIdx.x / kWaveSize;
     const int c = lane % kRowLanes;       // slice within the row
     const int rg = lane / kRowLanes;      // row group within the wave
 
     // Row group (wave, rg) owns kNormUnroll consecutive rows.
-    const int64_t first = chunk * kNormRowsPerBlock + (wave * kRowsPerWaveLoad + rg) * kNormUnroll;
-    const char* head_base = K + head * head_stride_bytes;
+    const int local = (wave * kRowsPerWaveLoad + rg) * kNormUnroll;          // first of them, within the block
+    const int64_t first = chunk * kNormRowsPerBlock + local;
 
+    // The block's rows through a buffer descriptor: the base is uniform (scalar arithmetic),
+    // the lanes add 32-bit offsets, and rows past the end of the head read as zero (their
+    // results are not stored), so the short-lived workgroups spend no vector instructions on
+    // 64-bit addresses or on clamping.
+    const int64_t left = T - chunk * kNormRowsPerBlock;                       // rows of the head from here on
+    const int rows_here = left < kNormRowsPerBlock ? (int)left : kNormRowsPerBlock;
+    const __amdgpu_buffer_rsrc_t rows = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(K + head * head_stride_bytes + chunk * (int64_t)(kNormRowsPerBlock * S::kRowBytes)), 0,
+        rows_here * S::kRowBytes, kRawBufferWord3);
     Words<S::kWords> raw[kNormUnroll];
 #pragma unroll
-    for (int u = 0; u < kNormUnroll; ++u) {
-        int64_t row = first + u;
-        row = row < T ? row : T - 1;      // tail: re-read the last row, result unused
-        const char* p = head_base + row * S::kRowBytes + c * P::kBytes;
-        if constexpr (kKeep) raw[u] = load_words<S::kWords, P::kStride>(p);
-        else raw[u] = load_words_stream<S::kWords, P::kStride>(p);
-    }
+    for (int u = 0; u < kNormUnroll; ++u)
+        raw[u] = buffer_load_words<S::kWords, P::kStride, kKeep ? kBufferPolicyPlain : kBufferPolicyStream>(
+            rows, (local + u) * S::kRowBytes + c * P::kBytes);
 
     float mine = 0.f;
 #pragma unroll
@@ -126,8 +133,10 @@ void norms_row_pairs_kernel(const char* __restrict__ K, int64_t T, int64_t head_
                             int64_t blocks_per_head, float* __restrict__ norms) {
 #pragma clang fp contract(off)
     constexpr int kRowBytes = 128;
-    const int64_t head = blockIdx.x / blocks_per_head;
-    const int64_t chunk = blockIdx.x % blocks_per_head;
+    // grid (chunks, heads) when the head count fits the y dimension; else one long x dimension
+    // cut by a 32-bit division (the launcher checked that the block count fits 31 bits)
+    const int64_t head = blocks_per_head == 0 ? blockIdx.y : blockIdx.x / (uint32_t)blocks_per_head;
+    const int64_t chunk = blocks_per_head == 0 ? blockIdx.x : blockIdx.x % (uint32_t)blocks_per_head;
     const int lane = threadIdx.x % kWaveSize;
     const int wave = threadIdx.x / kWaveSize;
     const int c = lane % kRowLanes;
@@ -183,8 +192,10 @@ static l2kv_status launch_norms(const void* K, int64_t n_heads, int64_t T, int64
     if (blocks > 0x7fffffffLL) return L2KV_ERR_SHAPE;
     auto kernel = keep_in_cache ? norms_kernel<E, D, true> : norms_kernel<E, D, false>;
     if constexpr (kPairs) kernel = keep_in_cache ? norms_row_pairs_kernel<true> : norms_row_pairs_kernel<false>;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kNormThreads), 0, stream,
-                       static_cast<const char*>(K), T, head_stride * (int64_t)E::kBytes, bph, norms);
+    const bool grid2d = n_heads <= 65535;
+    hipLaunchKernelGGL(kernel, grid2d ? dim3((unsigned)bph, (unsigned)n_heads) : dim3((unsigned)blocks),
+                       dim3(kNormThreads), 0, stream, static_cast<const char*>(K), T,
+                       head_stride * (int64_t)E::kBytes, grid2d ? (int64_t)0 : bph, norms);
     return launch_status();
 }
 

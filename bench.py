@@ -478,7 +478,8 @@ def main_stream(args, dev):
 def main_placement(args, dev):
     """Where the cache lies in device memory changes what the memory system delivers.  This probe
     (not a benchmark line) fills the memory with 1 GiB cache tensors in allocation order and
-    reports, per position: the read rate of the norm pass, and the time of a C3-shaped decode
+    reports, per position: the read rate of the norm pass, that of the bare read
+    (l2kv_read_probe), and the time of a C3-shaped decode
     launch (8 layers, B=4, 8 KV / 32 Q heads, 16384 rows, bf16) whose K and V are neighbours or a
     given number of GiB apart."""
     L, B, Hkv, Hq, n, D = 8, 4, 8, 32, 16384, 128
@@ -516,11 +517,14 @@ def main_placement(args, dev):
     for _ in range(20):                                                       # clocks up before the first figure
         decode_us(tensors[0], tensors[1])
     read = [round(tensor_bytes / timed(lambda t=t: l2kv.l2kv_norms(t, norms), 4) / 1e6) for t in tensors[::2]]
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    bare = [round(tensor_bytes / timed(lambda t=t: l2kv.l2kv_read_probe(t, sink), 4) / 1e6) for t in tensors[::2]]
     apart = args.placement_apart
     out = {
         "probe": "placement of the cache in device memory", "device_memory_GiB": round(total / 2**30, 1),
         "tensors_of_1GiB": count,
         "norm_pass_read_GBps_every_2nd_tensor": read,
+        "bare_read_GBps_every_2nd_tensor": bare,
         "decode_us_per_launch_K_V_neighbours": [decode_us(tensors[i], tensors[i + 1]) for i in range(0, count - 1, 2)],
         "decode_us_per_launch_K_V_%dGiB_apart" % apart: [decode_us(tensors[i], tensors[i + apart])
                                                          for i in range(0, count - apart, 2)],
@@ -717,6 +721,18 @@ def run_uniform(cfg, dev, steps, warmup, overridden, decode_splits, copy_probe, 
     # the norm pass is this library's own pure read stream (it reads K once and writes 1.6 % of
     # that): what a read-only kernel reaches on this machine in this run
     read_stream = nb * cfg.L / norms_ms / 1e6
+    # the bare read of the same K tensor (nothing computed, nothing stored): the ceiling of this
+    # buffer on this machine in this run
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    probe_ms = []
+    for _ in range(5):
+        a, b = ev(), ev()
+        a.record()
+        l2kv.l2kv_read_probe(w.K, sink)
+        b.record()
+        torch.cuda.synchronize()
+        probe_ms.append(a.elapsed_time(b))
+    read_probe = w.K.numel() * w.K.element_size() / float(np.median(probe_ms[1:])) / 1e6
 
     out = {
         "metric": "compress+decode effective HBM GB/s",
@@ -752,7 +768,10 @@ def run_uniform(cfg, dev, steps, warmup, overridden, decode_splits, copy_probe, 
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "read_stream_GBps": round(read_stream, 1),
             "pct_of_read_stream": round(100.0 * achieved / read_stream, 1),
-            "read_stream": "the norm pass of the same run (reads K once): the read-only rate reached here",
+            "read_stream": "the norm pass of the same run (reads K once and stores one float per row)",
+            "read_probe_GBps": round(read_probe, 1),
+            "pct_of_read_probe": round(100.0 * achieved / read_probe, 1),
+            "read_probe": "l2kv_read_probe over the same K tensor after the timed steps: loads only, no store",
             "traffic": PROFILED_DECODE_TRAFFIC_BYTES.get((cfg.dtype, cfg.B, cfg.Hkv, cfg.Hq, cfg.D, k)),
             "traffic_unit": "bytes per launch; constant from an offline rocprofv3 --pmc profile "
                             "(profiles/hot_path_hbm_traffic_pmc.md), not measured by this run",

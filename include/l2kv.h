@@ -467,6 +467,19 @@ l2kv_status l2kv_alr(const void* Q, const void* K, l2kv_dtype dt, const int32_t*
 size_t l2kv_alr_workspace_bytes(int32_t B, int32_t Hq, int64_t T);
 
 /*
+ * Measurement aid: streams `bytes` bytes from `data` (rounded down to a
+ * multiple of 8192) through the compute units with the loads of the norm
+ * pass, computes nothing and stores nothing -- the rate this launch reaches is
+ * the read-stream ceiling of the device for that buffer, against which the
+ * kernels above can be judged (it depends on where the buffer lies in device
+ * memory).  `sink`: 4 writable device bytes; written only if a block of the
+ * data XORs to one particular 32-bit value, which keeps the loads alive.
+ * Errors: NULL, ALIGN (data 16, sink 4), SHAPE (fewer than 8192 bytes, or
+ * more than 2^31 - 1 blocks of 8192), LAUNCH.
+ */
+l2kv_status l2kv_read_probe(const void* data, size_t bytes, uint32_t* sink, void* stream);
+
+/*
  * What the current HIP device reports about itself (host function, no kernel):
  * compute units, peak memory clock in kHz and memory bus width in bits, so
  * that a benchmark can print them next to the bandwidth peak it assumes.  Any

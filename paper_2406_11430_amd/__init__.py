@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     l2kv_select_workspace_bytes, l2kv_version, l2kv_select_ragged, l2kv_compact_ragged,
     l2kv_stream_append, l2kv_stream_evict, l2kv_decode_attn_ragged, l2kv_decode_ragged_workspace_bytes, l2kv_random_keys, l2kv_decode_workspace_init,
     l2kv_norm_ranks, l2kv_norm_ranks_workspace_bytes, l2kv_alr, l2kv_alr_workspace_bytes,
-    l2kv_length_order, l2kv_decode_attn_static, l2kv_device_info, l2kv_compress, l2kv_decode_attn_out,
+    l2kv_length_order, l2kv_decode_attn_static, l2kv_device_info, l2kv_compress, l2kv_decode_attn_out, l2kv_read_probe,
 )

@@ -78,6 +78,7 @@ SIGNATURES = {
                            C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "l2kv_alr_workspace_bytes": (C.c_size_t, [C.c_int32, C.c_int32, C.c_int64]),
     "l2kv_device_info": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "l2kv_read_probe": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
     "l2kv_status_string": (C.c_char_p, [C.c_int]),
     "l2kv_version": (C.c_int32, []),
 }
@@ -162,6 +163,14 @@ def l2kv_decode_workspace_init(workspace: torch.Tensor, stream=None) -> None:
     _dev(workspace)
     _check("l2kv_decode_workspace_init", lib().l2kv_decode_workspace_init(
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def l2kv_read_probe(data: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    """Stream `data` once through the compute units (bare read, nothing stored): a launch whose
+    rate is the read-stream ceiling for that buffer.  `sink`: any device tensor of >= 4 bytes."""
+    _dev(data, sink)
+    _check("l2kv_read_probe", lib().l2kv_read_probe(_ptr(data), data.numel() * data.element_size(),
+                                                     _ptr(sink), _stream(stream)))
 
 
 def l2kv_device_info() -> dict:

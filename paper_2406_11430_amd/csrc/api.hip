@@ -456,6 +456,12 @@ l2kv_status l2kv_alr(const void* Q, const void* K, l2kv_dtype dt, const int32_t*
                         workspace, static_cast<hipStream_t>(stream));
 }
 
+l2kv_status l2kv_read_probe(const void* data, size_t bytes, uint32_t* sink, void* stream) {
+    if (data == nullptr || sink == nullptr) return L2KV_ERR_NULL;
+    if (!aligned(data, 16) || !aligned(sink, 4)) return L2KV_ERR_ALIGN;
+    return read_probe_dispatch(data, bytes, sink, static_cast<hipStream_t>(stream));
+}
+
 l2kv_status l2kv_device_info(int32_t* h_compute_units, int32_t* h_memory_clock_khz, int32_t* h_memory_bus_bits) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) {

@@ -16,6 +16,7 @@ inline l2kv_status launch_status() {
 // Compute units of the current device (cached per device id).
 int device_compute_units();
 
+l2kv_status read_probe_dispatch(const void* data, size_t bytes, uint32_t* sink, hipStream_t stream);
 l2kv_status norms_dispatch(const void* K, l2kv_dtype dt, int64_t n_heads, int64_t T, int32_t D,
                            int64_t head_stride, float* norms, bool keep_in_cache, hipStream_t stream);
 

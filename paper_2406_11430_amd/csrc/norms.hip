@@ -199,6 +199,30 @@ static l2kv_status launch_norms(const void* K, int64_t n_heads, int64_t T, int64
     return launch_status();
 }
 
+// Measurement aid: the bare read stream.  Same access pattern as the norm pass (256 lanes, two
+// 16-byte non-temporal loads each, 8 KiB per workgroup), nothing computed but an XOR over the
+// lanes, nothing stored (the store below needs a 32-bit coincidence).  What it reaches is the
+// ceiling for any kernel that streams this buffer once.
+constexpr int kProbeBytesPerBlock = kNormThreads * 16 * 2;
+__global__ __launch_bounds__(kNormThreads)
+void read_probe_kernel(const char* __restrict__ data, uint32_t* __restrict__ sink) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const __amdgpu_buffer_rsrc_t block = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(data + (int64_t)blockIdx.x * kProbeBytesPerBlock), 0, kProbeBytesPerBlock, kRawBufferWord3);
+    const u32x4 a = __builtin_amdgcn_raw_buffer_load_b128(block, (int)threadIdx.x * 16, 0, kBufferPolicyStream);
+    const u32x4 b = __builtin_amdgcn_raw_buffer_load_b128(block, (int)threadIdx.x * 16 + kNormThreads * 16, 0, kBufferPolicyStream);
+    const uint32_t x = a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w;
+    if (x == 0x9E3779B9u) sink[0] = x;
+}
+
+l2kv_status read_probe_dispatch(const void* data, size_t bytes, uint32_t* sink, hipStream_t stream) {
+    const size_t blocks = bytes / kProbeBytesPerBlock;
+    if (blocks == 0 || blocks > 0x7fffffffULL) return L2KV_ERR_SHAPE;
+    hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)blocks), dim3(kNormThreads), 0, stream,
+                       static_cast<const char*>(data), sink);
+    return launch_status();
+}
+
 l2kv_status norms_dispatch(const void* K, l2kv_dtype dt, int64_t n_heads, int64_t T, int32_t D,
                            int64_t head_stride, float* norms, bool keep_in_cache, hipStream_t stream) {
     if (dt == L2KV_F32) {

@@ -235,6 +235,16 @@ def test_workspace_init_and_random_keys_validation(lib):
         assert lib.l2kv_decode_workspace_bytes(B, Hq, n, D) % 16 == 0
 
 
+def test_read_probe_validation(lib):
+    f = lib.l2kv_read_probe
+    assert f(None, 1 << 20, P, None) == E_NULL
+    assert f(P, 1 << 20, None, None) == E_NULL
+    assert f(P + 8, 1 << 20, P, None) == E_ALIGN
+    assert f(P, 1 << 20, P + 2, None) == E_ALIGN
+    assert f(P, 8191, P, None) == E_SHAPE            # less than one block of 8192 bytes
+    assert f(P, 8192 << 31, P, None) == E_SHAPE      # more blocks than a grid holds
+
+
 def test_decode_max_splits(lib):
     assert lib.l2kv_decode_max_splits(0) == 0
     assert lib.l2kv_decode_max_splits(1) == 1

@@ -792,3 +792,19 @@ def test_random_shapes_rows_of_128_and_512_bytes(dev):
         for ns in {0, 1, int(rng.integers(1, smax + 1)), smax}:
             got = gpu_decode(to_dev(Q, dt, dev), Kcd, Vcd, n_splits=ns).cpu().numpy()
             assert np.abs(got - want).max() <= ATTN_BAR, (case, dt, D, B, Hkv, G, T, k, ns)
+
+
+def test_read_probe_reads_whole_blocks_only_and_stores_nothing(dev):
+    """The measurement aid touches nothing: the sink stays as it was whatever the data (a store
+    needs one particular 32-bit XOR of a block), a tail below one block of 8192 bytes is not
+    read, and a buffer smaller than one block is refused."""
+    g = torch.Generator(device="cpu").manual_seed(77)
+    data = torch.randint(-2**31, 2**31 - 1, (3 * 2048 + 100,), dtype=torch.int32, generator=g).to(dev)
+    sink = torch.full((4,), 7, dtype=torch.int32, device=dev)
+    l2kv.l2kv_read_probe(data, sink)
+    l2kv.l2kv_read_probe(torch.zeros(1 << 20, dtype=torch.int32, device=dev), sink)
+    torch.cuda.synchronize()
+    assert sink.tolist() == [7, 7, 7, 7]
+    with pytest.raises(l2kv.L2KVError) as e:
+        l2kv.l2kv_read_probe(data[:2000], sink)
+    assert e.value.status == -2

@@ -555,21 +555,21 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
     // (if any) is handled by its owner afterwards with clamped loads and
     // masked scores.
     {
-        const int64_t n_full = kv_len / Geo::kTileRows;                         // full tiles in the head
-        const int64_t first_tile = (int64_t)split * kDecWaves + wave;
-        const int64_t tile_stride = (int64_t)n_splits * kDecWaves;
-        const int64_t mine = n_full > first_tile ? (n_full - first_tile + tile_stride - 1) / tile_stride : 0;
-        const int64_t kStride = tile_stride * Geo::kTileRows;                  // rows between my tiles
-        int64_t row = first_tile * Geo::kTileRows;
-        if (mine > 0) {
+        // Tile indices fit 32 bits (the host admits at most 2^31 - 1 rows) and the loop runs on
+        // comparisons of them: no division stands between the launch and the first load.
+        const int n_full = (int)(kv_len / Geo::kTileRows);                      // full tiles in the head
+        const int tile_stride = n_splits * kDecWaves;
+        int tile = split * kDecWaves + wave;                                     // my next tile
+        const int64_t kStride = (int64_t)tile_stride * Geo::kTileRows;          // rows between my tiles
+        int64_t row = (int64_t)tile * Geo::kTileRows;
+        if (tile < n_full) {
             Tile<E, D> ta, tb;
             // The scheduling barriers pin each batch of loads ahead of the
             // arithmetic on the other tile; without them the compiler sinks
             // the loads next to their first use and the prefetch is lost.
             load_tile<E, D>(ta, Kh, Vh, row, lane_off);
             __builtin_amdgcn_sched_barrier(0);
-            int64_t left = mine;                       // tiles not yet consumed; ta holds the first
-            while (left > 2) {
+            while (tile + 2 * tile_stride < n_full) {    // ta holds `tile`; at least two more follow
                 load_tile<E, D>(tb, Kh, Vh, row + kStride, lane_off);
                 __builtin_amdgcn_sched_barrier(0);
                 consume(ta, row, false);
@@ -579,21 +579,24 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
                 consume(tb, row + kStride, false);
                 __builtin_amdgcn_sched_barrier(0);
                 row += 2 * kStride;
-                left -= 2;
+                tile += 2 * tile_stride;
             }
-            if (left == 2) {
+            if (tile + tile_stride < n_full) {
                 load_tile<E, D>(tb, Kh, Vh, row + kStride, lane_off);
                 __builtin_amdgcn_sched_barrier(0);
                 consume(ta, row, false);
                 consume(tb, row + kStride, false);
+                tile += 2 * tile_stride;
             } else {
                 consume(ta, row, false);
+                tile += tile_stride;
             }
         }
-        if (kv_len % Geo::kTileRows != 0 && (n_full / kDecWaves) % n_splits == split &&
-            n_full % kDecWaves == wave) {
+        // `tile` is now the first tile of this wave's sequence at or past the full ones: the
+        // ragged last tile of the head, if there is one, belongs to the wave whose sequence hits it
+        if (kv_len % Geo::kTileRows != 0 && tile == n_full) {
             Tile<E, D> tt;
-            const int64_t first = n_full * Geo::kTileRows;
+            const int64_t first = (int64_t)n_full * Geo::kTileRows;
             load_tile_clamped<E, D>(tt, Kh, Vh, first, r1 - 1, rg, c);
             consume(tt, first, true);
         }
@@ -894,8 +897,8 @@ __device__ __forceinline__ void decode_item(const char* __restrict__ Q, const ch
     __syncthreads();              // the LDS tables may be reused by the caller's next item
 }
 
-// Grid launch: blockIdx.x = share of the KV head, blockIdx.y = (sequence or
-// position in the launch order) x KV head.
+// Grid launch: blockIdx.x = share of the KV head, blockIdx.y = KV head, blockIdx.z = sequence
+// (or position in the launch order); workgroups are dispatched with x running fastest, then y.
 template <typename E, int D, int G, bool kWideMerge>
 __global__ __launch_bounds__(kDecThreads) __attribute__((amdgpu_waves_per_eu(kDecodeMinWaves<E, D, G>)))
 void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
@@ -906,14 +909,20 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
                    float scale_log2e, uint32_t* __restrict__ counters,
                    float* __restrict__ partial, float* __restrict__ O, int out_bf16) {
     using S = Slice<E, D>;
+    // All arguments into scalar registers at once: one batch of loads and one wait, instead of
+    // a load and a wait wherever the code below first touches an argument (each of those is a
+    // round trip before the first row can be requested).
+    asm volatile("" ::"s"(Q), "s"(Kc), "s"(Vc), "s"(Hkv), "s"(kv_len_uniform), "s"(head_stride_bytes), "s"(lens),
+                 "s"(slot_off), "s"(seq_order), "s"(n_splits_grid), "s"(rows_per_wg), "s"(scale_log2e),
+                 "s"(counters), "s"(partial), "s"(O), "s"(out_bf16));
     const int split = blockIdx.x;
-    const int pair = blockIdx.y;                 // b * Hkv + hkv
-    const int hkv = pair % Hkv;
+    const int hkv = blockIdx.y;
+    const int pair = blockIdx.z * Hkv + hkv;     // b * Hkv + hkv
     // Ragged batches may come with a processing order (longest sequence first):
     // the launch index then names a position in that order, not the sequence.
-    int b = pair / Hkv;
+    int b = blockIdx.z;
     if (seq_order != nullptr) {
-        const int n_seq = (int)gridDim.y / Hkv;
+        const int n_seq = (int)gridDim.z;
         const int ob = seq_order[b];
         b = ob < 0 ? 0 : (ob < n_seq ? ob : n_seq - 1);
     }
@@ -936,8 +945,8 @@ void decode_kernel(const char* __restrict__ Q, const char* __restrict__ Kc,
         kv_len = lens[b];
         kv_len = kv_len < 0 ? 0 : (kv_len > slots.count ? slots.count : kv_len);
         slab = (int64_t)hkv * head_stride_bytes + slots.first * (int64_t)S::kRowBytes;
-        const int64_t need = (kv_len + rows_per_wg - 1) / rows_per_wg;
-        n_splits = need < 1 ? 1 : (need < n_splits_grid ? (int)need : n_splits_grid);
+        const int need = (int)(((uint32_t)kv_len + (uint32_t)rows_per_wg - 1u) / (uint32_t)rows_per_wg);   // kv_len is a clamped int32 here
+        n_splits = need < 1 ? 1 : (need < n_splits_grid ? need : n_splits_grid);
         if (split >= n_splits) return;
     }
     uint32_t unused = 0;
@@ -965,6 +974,10 @@ void decode_worklist_kernel(const char* __restrict__ Q, const char* __restrict__
                             float scale_log2e, uint32_t* __restrict__ counters, uint32_t* __restrict__ queue,
                             float* __restrict__ partial, float* __restrict__ O, int out_bf16) {
     using S = Slice<E, D>;
+    // all arguments into scalar registers with one batch of loads (see decode_kernel)
+    asm volatile("" ::"s"(Q), "s"(Kc), "s"(Vc), "s"(Hkv), "s"(n_seq), "s"(plane_stride_bytes), "s"(lens),
+                 "s"(slot_off), "s"(seq_order), "s"(n_splits_grid), "s"(rows_per_wg), "s"(scale_log2e),
+                 "s"(counters), "s"(queue), "s"(partial), "s"(O), "s"(out_bf16));
     __shared__ uint32_t s_item;
     const uint32_t n_items = (uint32_t)n_seq * (uint32_t)Hkv * (uint32_t)n_splits_grid;
     const int Hq = Hkv * G;
@@ -987,8 +1000,8 @@ void decode_worklist_kernel(const char* __restrict__ Q, const char* __restrict__
         int64_t kv_len = lens[b];
         kv_len = kv_len < 0 ? 0 : (kv_len > slots.count ? slots.count : kv_len);
         const int64_t slab = (int64_t)hkv * plane_stride_bytes + slots.first * (int64_t)S::kRowBytes;
-        const int64_t need = (kv_len + rows_per_wg - 1) / rows_per_wg;
-        const int n_splits = need < 1 ? 1 : (need < n_splits_grid ? (int)need : n_splits_grid);
+        const int need = (int)(((uint32_t)kv_len + (uint32_t)rows_per_wg - 1u) / (uint32_t)rows_per_wg);   // kv_len is a clamped int32 here
+        const int n_splits = need < 1 ? 1 : (need < n_splits_grid ? need : n_splits_grid);
         if (split >= n_splits) {                          // uniform: the whole workgroup skips the item
             if (threadIdx.x == 0)
                 drawn = gridDim.x + __hip_atomic_fetch_add(&queue[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1032,7 +1045,7 @@ l2kv_status launch_decode(const void* Q, const void* Kc, const void* Vc, int32_t
                            (int)plan.n_splits, (int)plan.rows_per_wg, scale_log2e, counters, queue, partial, O, (int)plan.out_bf16);
         return launch_status();
     }
-    dim3 grid((unsigned)plan.n_splits, (unsigned)(B * Hkv));
+    dim3 grid((unsigned)plan.n_splits, (unsigned)Hkv, (unsigned)B);
     auto kernel = wide ? decode_kernel<E, D, G, true> : decode_kernel<E, D, G, false>;
     hipLaunchKernelGGL(kernel, grid, dim3(kDecThreads), 0, stream,
                        static_cast<const char*>(Q), static_cast<const char*>(Kc),

@@ -47,7 +47,9 @@ class Batch:
         self.in_off = offsets(lens)
         ks = [min(n, self.budget_fn(n, s)) if n > 0 else 0 for s, n in enumerate(lens)]   # prompt compressed to its budget
         self.out_off = offsets(ks)
-        caps = [max(self.budget_fn(n + t, s) for t in range(steps + 1)) + 1 if n > 0 else 1
+        # room for the largest budget of any step plus the token appended before the eviction
+        # (an empty prompt grows like any other sequence: budget 0 before its first token)
+        caps = [max(self.budget_fn(n + t, s) if n + t > 0 else 0 for t in range(steps + 1)) + 1
                 for s, n in enumerate(lens)]
         self.slot_off = offsets(caps)
         total, total_kept, total_slots = int(self.in_off[-1]), int(self.out_off[-1]), int(self.slot_off[-1])
@@ -105,7 +107,6 @@ class Batch:
 
     def step(self, rng, t, n_splits=0, ordered=False):
         dev, D, L, Hkv, G = self.dev, self.D, self.L, self.Hkv, self.G
-        live = [s for s, n in enumerate(self.lens0) if n > 0]
         Kn = rows(rng, (L, self.n_seq, Hkv, D), self.dt)
         Vn = rows(rng, (L, self.n_seq, Hkv, D), self.dt)
         tok = torch.tensor([n + t for n in self.lens0], dtype=torch.int32, device=dev)
@@ -158,6 +159,15 @@ def test_stream_growing_budget(dev, dt, D):
     b = Batch(dev, rng, dt, D, L=2, Hkv=2, G=2, lens=[70, 1, 333, 64, 129], r=0.5, steps=12)
     for t in range(12):
         b.step(rng, t)
+
+
+def test_stream_sequences_that_start_empty(dev):
+    # empty prompts in a batch: nothing to select or compact for them, then they grow token by
+    # token like the others (append, attend over 1, 2, ... rows, evict to the growing budget)
+    rng = np.random.default_rng(40)
+    b = Batch(dev, rng, "bf16", 128, L=1, Hkv=2, G=4, lens=[0, 37, 0, 5], r=0.5, steps=7)
+    for t in range(7):
+        b.step(rng, t, n_splits=t % 2, ordered=bool(t % 2))
 
 
 def test_stream_fixed_budget_with_ties_equals_one_shot_select(dev):

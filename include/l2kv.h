@@ -365,14 +365,15 @@ l2kv_status l2kv_stream_evict(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, in
  *             sequence first (l2kv_length_order) the library hands whole
  *             (sequence, KV head) pairs, longest first, to one workgroup per
  *             compute unit, whichever is free next (a work list in the
- *             workspace), which is faster on batches of mixed lengths.  It only
- *             steers scheduling:
+ *             workspace), which is faster on batches of mixed lengths (bf16
+ *             caches with heads of 128 elements; other row sizes are launched
+ *             as a grid in the given order).  It only steers scheduling:
  *             outputs land at the sequence's own rows of O in any case.  An
  *             array that is not a permutation computes some sequences twice
  *             and others not at all (entries are forced into 0..n_seq-1).
  *             The order may be stale (lengths change from step to step).
  *             NULL: batches of 2..512 sequences whose longest has 2048 rows or
- *             more get a longest-first order worked out inside the call (one
+ *             more (bf16, D = 128) get a longest-first order worked out inside the call (one
  *             small extra kernel, about 7 us per call on an MI355X); all other
  *             batches are launched in batch order.  Either way the call is
  *             made of plain kernel launches and may be captured into a graph.

@@ -356,6 +356,10 @@ l2kv_status l2kv_stream_evict(l2kv_dtype dt, int32_t n_planes, int32_t n_seq, in
 static size_t ragged_order_bytes(int32_t n_seq) {
     return (static_cast<size_t>(n_seq) * sizeof(int32_t) + 255) / 256 * 256;
 }
+// Row size on which ordered batches take the work list (every (sequence, KV head, share) drawn
+// from a device counter): bf16 heads of 128 elements, the shape its tests and the streaming
+// benchmark cover.  Other row sizes are launched as a grid in the order given.
+static bool work_list_rows(l2kv_dtype dt, int32_t D) { return dt == L2KV_BF16 && D == 128; }
 constexpr int32_t kSelfOrderMaxSeq = 512;     // the set-up kernel is quadratic in n_seq
 constexpr int64_t kSelfOrderMinRows = 2048;   // below this the ordered plan is not used anyway
 
@@ -388,7 +392,7 @@ l2kv_status l2kv_decode_attn_ragged(const void* Q, const void* Kc, const void* V
         return L2KV_ERR_ALIGN;
     const float s = scale > 0.f ? scale : 1.0f / std::sqrt(static_cast<float>(D));
     if (seq_order == nullptr && n_splits == 0 && n_seq > 1 && n_seq <= kSelfOrderMaxSeq &&
-        max_len >= kSelfOrderMinRows) {
+        max_len >= kSelfOrderMinRows && work_list_rows(dt, D)) {
         // no order from the caller: a longest-first order is worked out here, per call, into the
         // tail of the workspace (a few microseconds; passing a stored order avoids them)
         int32_t* own_order = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) +
@@ -398,7 +402,8 @@ l2kv_status l2kv_decode_attn_ragged(const void* Q, const void* Kc, const void* V
             return st;
         seq_order = own_order;
     }
-    const DecodePlan plan = decode_plan_ragged(n_seq, Hkv, max_len, n_splits, seq_order != nullptr);
+    const DecodePlan plan = decode_plan_ragged(n_seq, Hkv, max_len, n_splits,
+                                               seq_order != nullptr && work_list_rows(dt, D));
     return decode_dispatch(Q, Kc, Vc, dt, n_seq, Hq, Hkv, max_len, D, total_slots * static_cast<int64_t>(D),
                            lens, slot_offsets, seq_order, s, plan, O, workspace,
                            static_cast<hipStream_t>(stream));

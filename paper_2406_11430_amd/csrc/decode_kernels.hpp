@@ -1052,15 +1052,19 @@ l2kv_status launch_decode(const void* Q, const void* Kc, const void* Vc, int32_t
     // two builds of each kernel: the final merge for at most 8 workgroups per KV head (all in
     // registers) or for more (tables in LDS); keeping both in one kernel slows the short one down
     const bool wide = plan.n_splits > 8;
-    if (plan.worklist_wgs > 0 && lens != nullptr && slot_off != nullptr && seq_order != nullptr) {
-        uint32_t* queue = counters + (size_t)B * (size_t)Hkv;     // two words behind the arrival counters
-        auto kernel = wide ? decode_worklist_kernel<E, D, G, true> : decode_worklist_kernel<E, D, G, false>;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)plan.worklist_wgs),
-                           dim3(kDecThreads), 0, stream, static_cast<const char*>(Q),
-                           static_cast<const char*>(Kc), static_cast<const char*>(Vc), (int)Hkv, (int)B,
-                           kv_head_stride * (int64_t)E::kBytes, lens, slot_off, seq_order,
-                           (int)plan.n_splits, (int)plan.rows_per_wg, scale_log2e, counters, queue, partial, O, (int)plan.out_bf16);
-        return launch_status();
+    // the work list exists for bf16 heads of 128 elements only (the host plans it for no other)
+    constexpr bool kWorkListRows = E::kBytes == 2 && D == 128;
+    if constexpr (kWorkListRows) {
+        if (plan.worklist_wgs > 0 && lens != nullptr && slot_off != nullptr && seq_order != nullptr) {
+            uint32_t* queue = counters + (size_t)B * (size_t)Hkv;     // two words behind the arrival counters
+            auto kernel = wide ? decode_worklist_kernel<E, D, G, true> : decode_worklist_kernel<E, D, G, false>;
+            hipLaunchKernelGGL(kernel, dim3((unsigned)plan.worklist_wgs),
+                               dim3(kDecThreads), 0, stream, static_cast<const char*>(Q),
+                               static_cast<const char*>(Kc), static_cast<const char*>(Vc), (int)Hkv, (int)B,
+                               kv_head_stride * (int64_t)E::kBytes, lens, slot_off, seq_order,
+                               (int)plan.n_splits, (int)plan.rows_per_wg, scale_log2e, counters, queue, partial, O, (int)plan.out_bf16);
+            return launch_status();
+        }
     }
     dim3 grid((unsigned)plan.n_splits, (unsigned)Hkv, (unsigned)B);
     auto kernel = wide ? decode_kernel<E, D, G, true> : decode_kernel<E, D, G, false>;
